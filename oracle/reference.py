@@ -1,0 +1,194 @@
+"""CPU ORACLE -- TEST INFRASTRUCTURE ONLY.
+
+Only tests/, the smoke check and the benchmark's cpu_baseline leg may import this module.  It
+shares nothing with the HIP path and never imports it.
+
+Contents (each cites the passage of the paper it follows):
+
+  spmm / spmm_rows        the definition Y = A.X in fp64 (Sec. 3.1, Fig. 2(a,b)); thin ctypes
+                          marshalling over spmm_oracle.c, which holds the three loops
+  features                input characteristics of Sec. 5.1, Table 2 (nnz, matrix size, standard
+                          deviation of row lengths, N) plus mean / max row length
+  conditional_reduction   the conditional prefix-sum network of Sec. 4 (EB+RM+PR, Fig. 6(e)),
+                          emulated lane by lane for any worker width
+  normalized_performance  the figure of merit of Fig. 1's caption / Sec. 5.1: per input,
+                          performance relative to the best algorithm on that input; geometric mean
+  tolerance_ratio, bit_mismatches   acceptance tests for an fp32 result against the fp64 oracle
+
+Pins (tests/test_oracle_pins.py): dense fp64 GEMM on tiny inputs, identity / permutation /
+diagonal matrices, empty rows, exact integer arithmetic against Python ints, closed forms (row
+normalised adjacency times ones; 27-point stencil neighbour counts), linearity and column
+independence, entry permutation / splitting, scipy's CSR product, and a literal pure-Python triple
+loop.  conditional_reduction is pinned against per-run sums computed by a scalar loop and by the
+paper's validity rule on the 6/2/0/3/1 example; normalized_performance against hand-computed
+two-input examples.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spmm_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile spmm_oracle.c into liboracle.so with the host C compiler."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, i64 = ctypes.c_void_p, ctypes.c_int64
+        lib.oracle_spmm.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp]
+        lib.oracle_spmm.restype = None
+        lib.oracle_spmm_rows.argtypes = [i64, vp, i64, vp, vp, vp, vp, vp, vp]
+        lib.oracle_spmm_rows.restype = None
+        lib.oracle_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _prep(rowptr, colind, vals, B):
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    if B.ndim != 2:
+        raise ValueError("B must be k x N")
+    if colind.size and (colind.min() < 0 or colind.max() >= B.shape[0]):
+        raise ValueError("column index outside [0, k)")
+    if rowptr[0] != 0 or rowptr[-1] != colind.size or np.any(np.diff(rowptr) < 0):
+        raise ValueError("malformed rowptr")
+    return rowptr, colind, vals, B
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+
+
+def spmm(rowptr, colind, vals, B, want_abs: bool = True):
+    """(C_ref, S_abs) as fp64 m x N arrays: the definition of Sec. 3.1 / Fig. 2 in double precision."""
+    rowptr, colind, vals, B = _prep(rowptr, colind, vals, B)
+    m, N = rowptr.size - 1, B.shape[1]
+    c = np.zeros((m, N), dtype=np.float64)
+    s = np.zeros((m, N), dtype=np.float64) if want_abs else None
+    if m and N:
+        _load().oracle_spmm(m, N, _p(rowptr), _p(colind), _p(vals), _p(B), _p(c), _p(s))
+    return c, s
+
+
+def spmm_rows(rows, rowptr, colind, vals, B, want_abs: bool = True):
+    """Rows `rows` of the product only (same loops as spmm); outputs are len(rows) x N."""
+    rowptr, colind, vals, B = _prep(rowptr, colind, vals, B)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    if rows.size and (rows.min() < 0 or rows.max() >= rowptr.size - 1):
+        raise ValueError("row id out of range")
+    N = B.shape[1]
+    c = np.zeros((rows.size, N), dtype=np.float64)
+    s = np.zeros((rows.size, N), dtype=np.float64) if want_abs else None
+    if rows.size and N:
+        _load().oracle_spmm_rows(rows.size, _p(rows), N, _p(rowptr), _p(colind), _p(vals), _p(B),
+                                 _p(c), _p(s))
+    return c, s
+
+
+# --------------------------------------------------------------------------------------------
+# input characteristics (Sec. 5.1, Table 2)
+# --------------------------------------------------------------------------------------------
+def features(rowptr, N: int) -> dict:
+    """rows (matrix size, read as the number of rows: all workloads are square), nnz, and the
+    mean / population standard deviation / maximum of the row lengths, and N."""
+    rp = np.asarray(rowptr, dtype=np.int64)
+    lens = np.diff(rp)
+    m = lens.size
+    if m == 0:
+        return dict(rows=0, nnz=0, row_nnz_mean=0.0, row_nnz_std=0.0, row_nnz_max=0.0, N=int(N))
+    mean = float(lens.sum()) / m
+    var = float(((lens.astype(np.float64) - mean) ** 2).sum()) / m
+    return dict(rows=int(m), nnz=int(lens.sum()), row_nnz_mean=mean, row_nnz_std=float(np.sqrt(var)),
+                row_nnz_max=float(lens.max()), N=int(N))
+
+
+# --------------------------------------------------------------------------------------------
+# conditional reduction (Sec. 4, EB+RM+PR, Fig. 6(e))
+# --------------------------------------------------------------------------------------------
+def conditional_reduction(partial, index):
+    """Emulate the conditional prefix-sum network on one worker of W = len(partial) lanes.
+
+    Every lane holds a partial result and an index flag naming its row; flags are non-decreasing
+    from left to right because stored entries are laid out row after row.  In step d = 1, 2, 4, ...
+    lane l takes in the value lane l+d held *before* the step, but only if both carry the same
+    flag (the datapath is "activated" only then).  Afterwards the value is valid at the leftmost
+    lane and at every lane whose flag differs from its left neighbour's: there it equals the sum of
+    the whole run of equal flags.  Returns (values after the last step, boolean validity mask).
+    """
+    v = np.array(partial, dtype=np.float64)
+    idx = np.asarray(index)
+    W = v.size
+    d = 1
+    while d < W:
+        prev = v.copy()
+        for lane in range(W):
+            if lane + d < W and idx[lane + d] == idx[lane]:
+                v[lane] = prev[lane] + prev[lane + d]
+        d *= 2
+    valid = np.ones(W, dtype=bool)
+    valid[1:] = idx[1:] != idx[:-1]
+    return v, valid
+
+
+# --------------------------------------------------------------------------------------------
+# figure of merit of the selector (Fig. 1 caption; Sec. 5.1)
+# --------------------------------------------------------------------------------------------
+def normalized_performance(times, chosen) -> float:
+    """times[i][a] = run time of algorithm a on input i; chosen[i] = algorithm picked for input i.
+    Performance is 1/time; each input's figure is perf(chosen)/perf(best on that input); the
+    inputs are combined by the geometric mean."""
+    t = np.asarray(times, dtype=np.float64)
+    ch = np.asarray(chosen, dtype=np.int64)
+    best = t.min(axis=1)
+    sel = t[np.arange(t.shape[0]), ch]
+    return float(np.exp(np.mean(np.log(best / sel))))
+
+
+# --------------------------------------------------------------------------------------------
+# acceptance tests for an fp32 result
+# --------------------------------------------------------------------------------------------
+REL_TOL = 1e-5
+ABS_TOL = 1e-6
+
+
+def tolerance_ratio(c, c_ref, s_abs) -> float:
+    """max over elements of |c - c_ref| / (1e-5 * S_abs + 1e-6); a result passes when <= 1."""
+    c = np.asarray(c, dtype=np.float64)
+    if c.size == 0:
+        return 0.0
+    if not np.all(np.isfinite(c)):
+        return float("inf")
+    return float(np.max(np.abs(c - c_ref) / (REL_TOL * s_abs + ABS_TOL)))
+
+
+def bit_mismatches(c, c_ref) -> int:
+    """Number of elements whose fp32 bit pattern differs from (float)c_ref, after mapping -0 to +0
+    (an exact zero sum may carry either sign depending on summation order)."""
+    a = np.ascontiguousarray(c, dtype=np.float32) + np.float32(0.0)
+    b = np.asarray(c_ref, dtype=np.float64).astype(np.float32) + np.float32(0.0)
+    return int(np.count_nonzero(a.view(np.uint32) != b.view(np.uint32)))
