@@ -1,0 +1,118 @@
+/*
+ * da_spmm.h -- C ABI of libdaspmm.so: data-aware CSR sparse x dense matrix multiply for
+ * AMD MI355X (gfx950, wave64).
+ *
+ * The operation is the paper's problem statement (Sec. 3.1, Fig. 2(b)):  Y = A * X  with A an
+ * M x K sparse matrix, X a K x N dense matrix and Y an M x N dense matrix; here named
+ * C = A * B with A in CSR form (m x k), B (k x N) and C (m x N) dense, row-major.
+ * Every algorithm id computes the same C (up to fp32 rounding order); the ids differ in how the
+ * three loops of Fig. 2(a) are mapped onto the machine (Sec. 3.2-3.4, Table 1) and the selector
+ * picks one of them from input characteristics (Sec. 5.1, Table 2).
+ *
+ * Conventions
+ *   - every pointer is a DEVICE pointer unless the comment says "host";
+ *   - buffers are borrowed for the duration of the stream-ordered execution of the call; the
+ *     caller owns and frees them; B and C must not overlap;
+ *   - calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and return without synchronising, except da_spmm_features which has to return
+ *     values to the host;
+ *   - every function returns a da_status (0 = success) and never throws or aborts;
+ *     da_spmm_last_error() gives a thread-local text for the last failure.
+ */
+#ifndef DA_SPMM_H
+#define DA_SPMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DA_OK = 0,
+    DA_ERR_INVALID_ARG = 1, /* negative size, size beyond the int32 index range, null rowptr / C */
+    DA_ERR_BAD_ALGO = 2,    /* algorithm id outside 0..7                                        */
+    DA_ERR_UNSUPPORTED = 3,
+    DA_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed                        */
+} da_status;
+
+/* Algorithm ids in the column order of the paper's Table 1:
+ *   M-loop  RB = row balance: a worker owns whole rows              (Sec. 3.2, design M1)
+ *           EB = element balance: a worker owns a fixed number of
+ *                consecutive stored entries                          (Sec. 3.2, design M2)
+ *   N-loop  RM = neighbouring lanes hold neighbouring columns n of one B row (coalesced row
+ *                segments, Sec. 3.3 design N1); CM = neighbouring lanes hold different rows /
+ *                entries and each lane walks its own strip of columns (Sec. 3.3 design N2).
+ *                B and C are row-major in memory for every id; the axis is the lane->n mapping.
+ *   K-loop  SR = one worker adds a row's products one after another  (Sec. 3.4, design K1)
+ *           PR = the lanes of a wave hold different entries and combine them with a reduction
+ *                tree; under EB this is the conditional reduction    (Sec. 3.4 design K2; Sec. 4)
+ */
+enum {
+    DA_RB_RM_SR = 0, DA_RB_RM_PR = 1, DA_RB_CM_SR = 2, DA_RB_CM_PR = 3,
+    DA_EB_RM_SR = 4, DA_EB_RM_PR = 5, DA_EB_CM_SR = 6, DA_EB_CM_PR = 7,
+    DA_NUM_ALGOS = 8
+};
+
+/* Input characteristics used by the selector (Sec. 5.1, Table 2: nnz, matrix size, standard
+ * deviation of the row lengths, N; extended by the mean and maximum row length).  Host struct. */
+typedef struct {
+    int64_t rows;          /* m                                                        */
+    int64_t nnz;           /* stored entries of A                                      */
+    double  row_nnz_mean;  /* nnz / m                                                  */
+    double  row_nnz_std;   /* population standard deviation (divide by m) of row length */
+    double  row_nnz_max;   /* longest row                                              */
+    int64_t N;             /* width of B and C                                         */
+} da_features;
+
+/*
+ * C = A * B  (Sec. 3.1, Fig. 2; algorithm space of Sec. 3.2-3.4 / Table 1, techniques of Sec. 4).
+ *
+ *   m, k, N   sizes; 0 <= m, k < 2^31, 0 <= N < 2^31.  m == 0 or N == 0 is a successful no-op.
+ *   rowptr    int32[m+1], rowptr[0] == 0, non-decreasing, rowptr[m] == nnz < 2^31
+ *   colind    int32[nnz], 0 <= colind[p] < k; need not be sorted inside a row; repeated (i,j)
+ *             entries add
+ *   vals      fp32[nnz]          (colind, vals and B may be NULL only when nnz == 0)
+ *   B         fp32[k*N], row-major, leading dimension N
+ *   C         fp32[m*N], row-major, leading dimension N; every element is OVERWRITTEN (rows
+ *             without stored entries become +0)
+ *   algo      0..7, see the enum above
+ *   stream    hipStream_t (NULL = default stream)
+ *
+ * The contents of rowptr / colind are not validated (they live on the device); indices outside
+ * their range are undefined behaviour.  EB ids enqueue two kernels (a pass that zeroes the rows
+ * which will receive atomic additions, then the product); results of ids that use atomics can
+ * differ in the last bits from run to run.  Returns DA_ERR_INVALID_ARG, DA_ERR_BAD_ALGO or
+ * DA_ERR_HIP on failure; nothing is enqueued for the first two.
+ */
+int da_spmm(int64_t m, int64_t k, int64_t N,
+            const int32_t *rowptr, const int32_t *colind, const float *vals,
+            const float *B, float *C, int algo, void *stream);
+
+/*
+ * Data-aware algorithm choice (Sec. 5.1): maps input characteristics to an algorithm id 0..7 by
+ * walking a decision tree compiled into the library (trained offline on this GPU on seeded
+ * synthetic matrices).  `f` is a HOST pointer.  Pure and deterministic; no device work.
+ * Returns the id, or a negative da_status (-DA_ERR_INVALID_ARG) when f is NULL or holds
+ * negative / non-finite entries.
+ */
+int da_spmm_select(const da_features *f);
+
+/*
+ * Extract the selector's input characteristics (Sec. 5.1, Table 2) from the row pointers with one
+ * device reduction.  rowptr is a device pointer (int32[m+1]); `out` is a HOST pointer.  Blocks
+ * until the result is on the host (synchronises `stream`).  m == 0 gives all-zero features.
+ */
+int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, da_features *out);
+
+/* "RB+RM+SR" ... "EB+CM+PR" (Table 1 naming); NULL for an id outside 0..7.  Host string, static. */
+const char *da_spmm_algo_name(int algo);
+
+/* Text describing the last failure on the calling thread ("" if none).  Host string, valid until
+ * the next failing call on the same thread. */
+const char *da_spmm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DA_SPMM_H */

@@ -1,0 +1,118 @@
+"""Thin Python binding over the C ABI of libdaspmm.so (include/da_spmm.h).
+
+Argument marshalling only: every step of the SpMM path runs in the HIP kernels of the library.
+PyTorch is used for device memory and streams.  Importing this module loads the library and
+raises ImportError if it has not been built (python -m paper_2202_08556_amd.build); there is
+no CPU or PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # loads the HIP runtime the library links against
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdaspmm.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2202_08556_amd.build`")
+_lib = ctypes.CDLL(_LIB_PATH)
+
+DA_OK, DA_ERR_INVALID_ARG, DA_ERR_BAD_ALGO, DA_ERR_UNSUPPORTED, DA_ERR_HIP = range(5)
+(DA_RB_RM_SR, DA_RB_RM_PR, DA_RB_CM_SR, DA_RB_CM_PR,
+ DA_EB_RM_SR, DA_EB_RM_PR, DA_EB_CM_SR, DA_EB_CM_PR) = range(8)
+DA_NUM_ALGOS = 8
+EXPORTS = ("da_spmm", "da_spmm_select", "da_spmm_features", "da_spmm_algo_name", "da_spmm_last_error")
+
+
+class da_features(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("row_nnz_mean", ctypes.c_double), ("row_nnz_std", ctypes.c_double),
+                ("row_nnz_max", ctypes.c_double), ("N", ctypes.c_int64)]
+
+
+_vp, _i64 = ctypes.c_void_p, ctypes.c_int64
+_lib.da_spmm.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _vp]
+_lib.da_spmm.restype = ctypes.c_int
+_lib.da_spmm_select.argtypes = [ctypes.POINTER(da_features)]
+_lib.da_spmm_select.restype = ctypes.c_int
+_lib.da_spmm_features.argtypes = [_i64, _i64, _vp, _vp, ctypes.POINTER(da_features)]
+_lib.da_spmm_features.restype = ctypes.c_int
+_lib.da_spmm_algo_name.argtypes = [ctypes.c_int]
+_lib.da_spmm_algo_name.restype = ctypes.c_char_p
+_lib.da_spmm_last_error.argtypes = []
+_lib.da_spmm_last_error.restype = ctypes.c_char_p
+
+
+class DaSpmmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"da_spmm status {status}: {message}")
+        self.status = status
+
+
+def _ptr(x):
+    """Device address of a torch tensor, or an int / None passed through."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def da_spmm_last_error() -> str:
+    return _lib.da_spmm_last_error().decode()
+
+
+def da_spmm_status(m, k, N, rowptr, colind, vals, B, C, algo, stream=None) -> int:
+    """Raw call: returns the da_status instead of raising."""
+    return int(_lib.da_spmm(int(m), int(k), int(N), _ptr(rowptr), _ptr(colind), _ptr(vals),
+                            _ptr(B), _ptr(C), int(algo), _stream(stream)))
+
+
+def da_spmm(m, k, N, rowptr, colind, vals, B, C, algo, stream=None) -> None:
+    """C = A.B on the device; arguments as in include/da_spmm.h (torch CUDA tensors or addresses)."""
+    st = da_spmm_status(m, k, N, rowptr, colind, vals, B, C, algo, stream)
+    if st != DA_OK:
+        raise DaSpmmError(st, da_spmm_last_error())
+
+
+def _to_struct(f) -> da_features:
+    if isinstance(f, da_features):
+        return f
+    return da_features(int(f["rows"]), int(f["nnz"]), float(f["row_nnz_mean"]),
+                       float(f["row_nnz_std"]), float(f["row_nnz_max"]), int(f["N"]))
+
+
+def da_spmm_select(f) -> int:
+    """Algorithm id for the given features (dict with the fields of da_features, or the struct)."""
+    if f is None:
+        r = int(_lib.da_spmm_select(None))
+    else:
+        s = _to_struct(f)
+        r = int(_lib.da_spmm_select(ctypes.byref(s)))
+    if r < 0:
+        raise DaSpmmError(-r, "da_spmm_select: invalid features")
+    return r
+
+
+def da_spmm_features(m, N, rowptr, stream=None) -> dict:
+    out = da_features()
+    st = int(_lib.da_spmm_features(int(m), int(N), _ptr(rowptr), _stream(stream), ctypes.byref(out)))
+    if st != DA_OK:
+        raise DaSpmmError(st, da_spmm_last_error())
+    return {n: getattr(out, n) for n, _ in da_features._fields_}
+
+
+def da_spmm_algo_name(algo: int):
+    s = _lib.da_spmm_algo_name(int(algo))
+    return s.decode() if s is not None else None
+
+
+ALGO_NAMES = [da_spmm_algo_name(a) for a in range(DA_NUM_ALGOS)]

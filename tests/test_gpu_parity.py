@@ -1,0 +1,137 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Tolerance (fp32 result against the fp64 definition): |C - C_ref| <= 1e-5 * (|A|.|B|)_ij + 1e-6.
+Integer-valued inputs must match bit for bit (after mapping -0 to +0)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as orc
+from paper_2202_08556_amd import generators as gen
+
+pytestmark = pytest.mark.gpu
+
+ALGOS = list(range(8))
+
+
+def problems():
+    """Sizes the oracle finishes in well under a second each, spanning several tiles and chunks,
+    with ragged tails in m, nnz and N."""
+    yield "fig6a", gen.fig6a_csr(), [1, 3, 4, 8]
+    yield "uniform", gen.uniform_csr(seed=1000), [8, 33]
+    yield "uniform_ragged", gen.uniform_csr(m=1237, k=911, mean_len=11, seed=7), [1, 2, 6, 20, 64, 100]
+    yield "powerlaw", gen.powerlaw_csr(m=8192, seed=2001), [32, 128]
+    yield "stencil", gen.stencil27_csr(12, 13, 14, seed=3001), [32, 7]
+    yield "skewed", gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001), [8, 64]
+    yield "lognormal_cv4", gen.lognormal_csr(5000, 24.0, 4.0, seed=5100), [16, 256, 260]
+    yield "const_rows", gen.lognormal_csr(3000, 64.0, 0.0, seed=5101), [4, 48]
+    yield "one_long_row", gen.skewed_csr(m=64, k=40000, heavy_frac=0.02, heavy_lo=30000,
+                                         heavy_hi=30000, light_mean=0.5, seed=9), [8, 12]
+
+
+CASES = [(name, a, N) for name, a, Ns in problems() for N in Ns]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from tests.gpu_util import DeviceProblem
+    return DeviceProblem
+
+
+@pytest.mark.parametrize("name,a,N", CASES, ids=[f"{c[0]}-N{c[2]}" for c in CASES])
+def test_all_algorithms_match_oracle(gpu, name, a, N):
+    B = gen.dense(a.k, N, "normal" if "power" in name else "uniform", seed=a.seed + N)
+    c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
+    prob = gpu(a, B)
+    for algo in ALGOS:
+        print(f"case {name} N={N} algo={algo}", flush=True)
+        c = prob.run(algo)
+        ratio = orc.tolerance_ratio(c, c_ref, s_abs)
+        assert ratio <= 1.0, f"{name} N={N} algo={algo}: tolerance ratio {ratio}"
+        empty = a.row_lengths() == 0
+        assert np.all(c[empty].view(np.uint32) == 0), "rows without entries must be +0"
+
+
+@pytest.mark.parametrize("name,a,N", CASES, ids=[f"{c[0]}-N{c[2]}" for c in CASES])
+def test_integer_inputs_bit_exact(gpu, name, a, N):
+    ai = gen.integer_twin(a)
+    B = gen.dense_int(a.k, N, seed=a.seed + N)
+    c_ref, _ = orc.spmm(ai.rowptr, ai.colind, ai.vals, B, want_abs=False)
+    prob = gpu(ai, B)
+    for algo in ALGOS:
+        print(f"int case {name} N={N} algo={algo}", flush=True)
+        for rep in range(2):                      # atomics: order may vary, bits may not
+            c = prob.run(algo)
+            assert orc.bit_mismatches(c, c_ref) == 0, f"{name} N={N} algo={algo} rep={rep}"
+
+
+def test_unsorted_columns_and_duplicates(gpu):
+    a = gen.uniform_csr(m=700, k=500, mean_len=9, seed=21)
+    rng = np.random.Generator(np.random.PCG64(3))
+    ci, v = a.colind.copy(), a.vals.copy()
+    for i in range(a.m):
+        s, e = a.rowptr[i], a.rowptr[i + 1]
+        p = rng.permutation(e - s)
+        ci[s:e], v[s:e] = ci[s:e][p], v[s:e][p]
+    # duplicate every entry (halved values) so that repeated (i,j) must add
+    dup = gen.CSR(a.m, a.k, (a.rowptr.astype(np.int64) * 2).astype(np.int32), np.repeat(ci, 2),
+                  np.repeat(v * np.float32(0.5), 2), "dup", a.seed)
+    B = gen.dense(a.k, 12, "uniform", seed=4)
+    c_ref, s_abs = orc.spmm(dup.rowptr, dup.colind, dup.vals, B)
+    prob = gpu(dup, B)
+    for algo in ALGOS:
+        assert orc.tolerance_ratio(prob.run(algo), c_ref, s_abs) <= 1.0
+
+
+def test_degenerate_shapes(gpu):
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    # nnz == 0: C must be zero-filled by every algorithm
+    m, k, N = 300, 50, 24
+    a = gen.CSR(m, k, np.zeros(m + 1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32), "empty", 0)
+    B = gen.dense(k, N, "uniform", seed=1)
+    prob = gpu(a, B)
+    for algo in ALGOS:
+        assert not prob.run(algo).any()
+    # a single row and a single column
+    a = gen.uniform_csr(m=1, k=777, mean_len=300, seed=5)
+    B = gen.dense(a.k, 1, "uniform", seed=6)
+    c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
+    prob = gpu(a, B)
+    for algo in ALGOS:
+        assert orc.tolerance_ratio(prob.run(algo), c_ref, s_abs) <= 1.0
+    # m == 0 and N == 0 are no-ops that leave C untouched
+    C = torch.full((4, 4), 7.0, device=dev)
+    z = torch.zeros(1, dtype=torch.int32, device=dev)
+    da.da_spmm(0, 4, 4, z, z, C, C, C, 0)
+    da.da_spmm(4, 4, 0, z, z, C, C, C, 4)
+    torch.cuda.synchronize()
+    assert torch.all(C == 7.0)
+    # unaligned B / C base (offset by one float) forces the scalar-width path
+    a = gen.uniform_csr(m=500, k=400, mean_len=7, seed=8)
+    N = 8
+    Bh = gen.dense(a.k, N, "uniform", seed=9)
+    c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, Bh)
+    rp, ci, va = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals))
+    Bbuf = torch.zeros(a.k * N + 1, device=dev)
+    Bbuf[1:] = torch.from_numpy(Bh).to(dev).reshape(-1)
+    Cbuf = torch.full((a.m * N + 1,), float("nan"), device=dev)
+    for algo in ALGOS:
+        da.da_spmm(a.m, a.k, N, rp, ci, va, Bbuf.data_ptr() + 4, Cbuf.data_ptr() + 4, algo)
+        torch.cuda.synchronize()
+        c = Cbuf[1:].reshape(a.m, N).cpu().numpy()
+        assert orc.tolerance_ratio(c, c_ref, s_abs) <= 1.0
+
+
+def test_features_match_oracle(gpu):
+    from paper_2202_08556_amd import binding as da
+    for a in (gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001),
+              gen.lognormal_csr(5000, 24.0, 0.0, seed=1), gen.fig6a_csr()):
+        rp = torch.from_numpy(a.rowptr).to("cuda:0")
+        got = da.da_spmm_features(a.m, 32, rp)
+        want = orc.features(a.rowptr, 32)
+        assert got["rows"] == want["rows"] and got["nnz"] == want["nnz"] and got["N"] == 32
+        assert got["row_nnz_max"] == want["row_nnz_max"]
+        assert got["row_nnz_mean"] == pytest.approx(want["row_nnz_mean"], rel=1e-14)
+        assert got["row_nnz_std"] == pytest.approx(want["row_nnz_std"], rel=1e-9, abs=1e-12)
+        assert 0 <= da.da_spmm_select(got) < 8
