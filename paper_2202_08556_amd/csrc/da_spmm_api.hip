@@ -7,6 +7,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 namespace {
@@ -45,14 +46,6 @@ int pow2_ceil(long x) {
     return p;
 }
 
-// widest per-lane vector (technique 2 of Sec. 4) that N and the base addresses allow
-int pick_vec(int64_t N, const void* B, const void* C) {
-    const uintptr_t a = reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C);
-    if (N % 4 == 0 && a % 16 == 0) return 4;
-    if (N % 2 == 0 && a % 8 == 0) return 2;
-    return 1;
-}
-
 struct Problem {
     int m, N;
     const int* rowptr;
@@ -66,12 +59,66 @@ struct Problem {
 
 enum Family { RB_SR, RB_PR, EB_SR, EB_PR };
 
-constexpr int kEntriesPerWave = 512;   // EB: stored entries per wave and pass
-constexpr int kMaxGridY = 65535;
+// Launch geometry of one call: lane mapping (V, G, NV as in da_spmm_kernels.hip) and, for EB,
+// the number of stored entries per worker.
+struct Geometry {
+    int V, G, NV, chunk;
+};
 
-template <int V, int G>
-int launch(Family fam, const Problem& p) {
-    const long tiles_l = (p.N + (long)G * V - 1) / ((long)G * V);
+constexpr int kMaxGridY = 65535;
+constexpr int kMaxGroupPR = 8;         // RM mapping under PR keeps at least 8 slots along the entries
+constexpr int kEntriesPerWavePR = 512; // EB+PR: stored entries per wave and pass
+
+int env_int(const char* name, int fallback) {
+    const char* v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// Default geometry per algorithm family and N.  Measured on MI355X: 16-byte and 4-byte gathers
+// run at full rate, 8-byte gathers at about half, and narrow rows (N < 32) gather fastest with one
+// column per lane.  Setting DA_SPMM_TUNE=1 lets DA_SPMM_V / _G / _NV / _CHUNK override the choice
+// (for tuning runs only; invalid combinations are rejected).
+int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const void* C, Geometry* out) {
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C);
+    const bool vec4_ok = (N % 4 == 0) && (addr % 16 == 0);
+    Geometry g{1, 1, 1, 0};
+    if (cm) {
+        g.V = vec4_ok ? 4 : 1;
+        const long vecs = (N + g.V - 1) / g.V;
+        g.NV = vecs >= 4 ? 4 : pow2_ceil(vecs);
+        g.G = 1;
+    } else {
+        g.V = (vec4_ok && N >= 32) ? 4 : 1;
+        g.G = pow2_ceil((N + g.V - 1) / g.V);
+        const int cap = pr ? kMaxGroupPR : kWave;
+        if (g.G > cap) g.G = cap;
+        g.NV = 1;
+    }
+    static const bool tune = std::getenv("DA_SPMM_TUNE") != nullptr;
+    if (tune) {
+        g.V = env_int("DA_SPMM_V", g.V);
+        g.G = env_int("DA_SPMM_G", g.G);
+        g.NV = env_int("DA_SPMM_NV", g.NV);
+        if ((g.V != 1 && g.V != 4) || (g.V == 4 && !vec4_ok) || !is_pow2(g.G) || g.G > kWave ||
+            (pr && g.G > kMaxGroupPR) || (g.NV != 1 && g.NV != 2 && g.NV != 4) || (g.G > 1 && g.NV != 1))
+            return fail(DA_ERR_UNSUPPORTED, "DA_SPMM_V/_G/_NV override is not a supported combination%s");
+    }
+    if (eb) {
+        if (pr) g.chunk = kEntriesPerWavePR;
+        else g.chunk = g.G >= 8 ? 256 : (g.G == 4 ? 128 : 64);
+        if (tune) g.chunk = env_int("DA_SPMM_CHUNK", g.chunk);
+        if (g.chunk < 8 || g.chunk > (1 << 20)) return fail(DA_ERR_UNSUPPORTED, "bad DA_SPMM_CHUNK%s");
+    }
+    *out = g;
+    return DA_OK;
+}
+
+template <int V, int G, int NV>
+int launch(Family fam, const Problem& p, int chunk) {
+    const long tile_cols = (long)G * V * NV;
+    const long tiles_l = (p.N + tile_cols - 1) / tile_cols;
     if (tiles_l > kMaxGridY) return fail(DA_ERR_UNSUPPORTED, "N needs more than 65535 column tiles%s");
     const unsigned tiles = (unsigned)tiles_l;
     const dim3 block(kBlock);
@@ -79,21 +126,21 @@ int launch(Family fam, const Problem& p) {
     case RB_SR: {
         const long rows_per_block = (long)kWavesPerBlock * (kWave / G);
         const dim3 grid((unsigned)((p.m + rows_per_block - 1) / rows_per_block), tiles);
-        hipLaunchKernelGGL((rb_sr_kernel<V, G>), grid, block, 0, p.stream,
+        hipLaunchKernelGGL((rb_sr_kernel<V, G, NV>), grid, block, 0, p.stream,
                            p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C);
         break;
     }
     case RB_PR: {
-        const dim3 grid((unsigned)((p.m + kWavesPerBlock - 1) / kWavesPerBlock), tiles);
-        hipLaunchKernelGGL((rb_pr_kernel<V, G>), grid, block, 0, p.stream,
-                           p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C);
+        if constexpr (G <= kMaxGroupPR) {
+            const dim3 grid((unsigned)((p.m + kWavesPerBlock - 1) / kWavesPerBlock), tiles);
+            hipLaunchKernelGGL((rb_pr_kernel<V, G, NV>), grid, block, 0, p.stream,
+                               p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C);
+        }
         break;
     }
     case EB_SR:
     case EB_PR: {
-        // entries per worker: a lane group (SR) or a whole wave (PR)
-        const int chunk = fam == EB_SR ? (kEntriesPerWave * G / kWave < 8 ? 8 : kEntriesPerWave * G / kWave)
-                                       : kEntriesPerWave;
+        // entries per block and pass: a lane group (SR) or a whole wave (PR) owns `chunk` entries
         const long entries_per_block = fam == EB_SR ? (long)chunk * kWavesPerBlock * (kWave / G)
                                                     : (long)chunk * kWavesPerBlock;
         // nnz is known only on the device; size the grid for a full machine, bounded by what the
@@ -105,22 +152,17 @@ int launch(Family fam, const Problem& p) {
         if (blocks > full) blocks = full;
         if (blocks < 1) blocks = 1;
         // pre-pass: zero the rows that receive atomic additions, and the rows without entries
-        {
-            const int gz = pow2_ceil((p.N + V - 1) / V) > kWave ? kWave : pow2_ceil((p.N + V - 1) / V);
-            const long rows_per_block = (long)kWavesPerBlock * (kWave / gz);
-            const dim3 zgrid((unsigned)((p.m + rows_per_block - 1) / rows_per_block));
-#define DA_ZERO(GZ) case GZ: hipLaunchKernelGGL((eb_zero_kernel<V, GZ>), zgrid, block, 0, p.stream, \
-                                                p.m, p.N, p.rowptr, p.C, chunk); break;
-            switch (gz) { DA_ZERO(1) DA_ZERO(2) DA_ZERO(4) DA_ZERO(8) DA_ZERO(16) DA_ZERO(32) DA_ZERO(64) }
-#undef DA_ZERO
-        }
+        const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
+        hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.rowptr, p.C, chunk);
         const dim3 grid((unsigned)blocks, tiles);
-        if (fam == EB_SR)
-            hipLaunchKernelGGL((eb_sr_kernel<V, G>), grid, block, 0, p.stream,
+        if (fam == EB_SR) {
+            hipLaunchKernelGGL((eb_sr_kernel<V, G, NV>), grid, block, 0, p.stream,
                                p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk);
-        else
-            hipLaunchKernelGGL((eb_pr_kernel<V, G>), grid, block, 0, p.stream,
-                               p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk);
+        } else {
+            if constexpr (G <= kMaxGroupPR)
+                hipLaunchKernelGGL((eb_pr_kernel<V, G, NV>), grid, block, 0, p.stream,
+                                   p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk);
+        }
         break;
     }
     }
@@ -130,31 +172,34 @@ int launch(Family fam, const Problem& p) {
 }
 
 template <int V>
-int dispatch_g(Family fam, int G, const Problem& p) {
-    switch (G) {
-    case 1: return launch<V, 1>(fam, p);
-    case 2: return launch<V, 2>(fam, p);
-    case 4: return launch<V, 4>(fam, p);
-    case 8: return launch<V, 8>(fam, p);
-    case 16: return launch<V, 16>(fam, p);
-    case 32: return launch<V, 32>(fam, p);
-    case 64: return launch<V, 64>(fam, p);
+int dispatch_v(Family fam, const Geometry& g, const Problem& p) {
+    if (g.G == 1) {
+        switch (g.NV) {
+        case 1: return launch<V, 1, 1>(fam, p, g.chunk);
+        case 2: return launch<V, 1, 2>(fam, p, g.chunk);
+        case 4: return launch<V, 1, 4>(fam, p, g.chunk);
+        }
+    } else if (g.NV == 1) {
+        switch (g.G) {
+        case 2: return launch<V, 2, 1>(fam, p, g.chunk);
+        case 4: return launch<V, 4, 1>(fam, p, g.chunk);
+        case 8: return launch<V, 8, 1>(fam, p, g.chunk);
+        case 16: return launch<V, 16, 1>(fam, p, g.chunk);
+        case 32: return launch<V, 32, 1>(fam, p, g.chunk);
+        case 64: return launch<V, 64, 1>(fam, p, g.chunk);
+        }
     }
-    return fail(DA_ERR_UNSUPPORTED, "bad lane group%s");
+    return fail(DA_ERR_UNSUPPORTED, "unsupported lane mapping%s");
 }
 
-int dispatch(Family fam, int V, int G, const Problem& p) {
-    switch (V) {
-    case 4: return dispatch_g<4>(fam, G, p);
-    case 2: return dispatch_g<2>(fam, G, p);
-    default: return dispatch_g<1>(fam, G, p);
-    }
+int dispatch(Family fam, const Geometry& g, const Problem& p) {
+    if ((fam == RB_PR || fam == EB_PR) && g.G > kMaxGroupPR)
+        return fail(DA_ERR_UNSUPPORTED, "PR lane group too wide%s");
+    return g.V == 4 ? dispatch_v<4>(fam, g, p) : dispatch_v<1>(fam, g, p);
 }
 
 const char* const kNames[DA_NUM_ALGOS] = {
     "RB+RM+SR", "RB+RM+PR", "RB+CM+SR", "RB+CM+PR", "EB+RM+SR", "EB+RM+PR", "EB+CM+SR", "EB+CM+PR"};
-
-constexpr int kMaxGroupPR = 8;   // RM mapping under PR keeps at least 8 slots along the entries
 
 }  // namespace
 
@@ -173,18 +218,14 @@ int da_spmm(int64_t m, int64_t k, int64_t N, const int32_t* rowptr, const int32_
     // which only the device knows
 
     Problem p{(int)m, (int)N, rowptr, colind, vals, B, C, (hipStream_t)stream, k};
-    const int V = pick_vec(N, B, C);
     const bool eb = algo >= DA_EB_RM_SR;
     const bool cm = (algo & 2) != 0;
     const bool pr = (algo & 1) != 0;
-    int G = 1;
-    if (!cm) {
-        G = pow2_ceil((N + V - 1) / V);
-        const int cap = pr ? kMaxGroupPR : kWave;
-        if (G > cap) G = cap;
-    }
+    Geometry g;
+    const int st = pick_geometry(cm, pr, eb, N, B, C, &g);
+    if (st != DA_OK) return st;
     const Family fam = eb ? (pr ? EB_PR : EB_SR) : (pr ? RB_PR : RB_SR);
-    return dispatch(fam, V, G, p);
+    return dispatch(fam, g, p);
 }
 
 int da_spmm_features(int64_t m, int64_t N, const int32_t* rowptr, void* stream, da_features* out)

@@ -3,18 +3,22 @@
 // Four kernel templates cover the 8 algorithms of the paper's Table 1:
 //
 //                     K-loop SR (Sec. 3.4 K1)        K-loop PR (Sec. 3.4 K2, Sec. 4)
-//   M-loop RB (M1)    rb_sr_kernel<V,G>              rb_pr_kernel<V,G>
-//   M-loop EB (M2)    eb_sr_kernel<V,G>              eb_pr_kernel<V,G>   (conditional reduction)
+//   M-loop RB (M1)    rb_sr_kernel<V,G,NV>           rb_pr_kernel<V,G,NV>
+//   M-loop EB (M2)    eb_sr_kernel<V,G,NV>           eb_pr_kernel<V,G,NV>  (conditional reduction)
 //
-// The N-loop axis (Sec. 3.3) is the template parameter G = number of neighbouring lanes that share
-// one stored entry and hold neighbouring column vectors of the B row it points to:
-//   RM mapping: G = smallest power of two >= N/V (a lane group reads one contiguous B row segment)
-//   CM mapping: G = 1 (neighbouring lanes hold different rows / entries; each lane owns a strip of
-//               V columns; further strips are further grid.y tiles)
-// V = 1, 2 or 4 is the number of consecutive columns a lane loads at once (the float2/float4
-// technique of Sec. 4).  B and C are row-major in memory in every case.
+// The N-loop axis (Sec. 3.3) is the lane mapping, set by the template parameters:
+//   G   neighbouring lanes that share one stored entry and hold neighbouring column vectors of
+//       the B row it points to.  RM mapping: G > 1 (a lane group reads one contiguous B row
+//       segment, coalesced).  CM mapping: G = 1 (neighbouring lanes hold different rows / entries).
+//   V   consecutive columns a lane loads at once (the float2/float4 technique of Sec. 4): 1 or 4.
+//   NV  vectors of V columns a lane walks one after another (CM: the lane's own strip of columns;
+//       RM uses NV = 1).
+// A lane group covers G*V*NV columns; blockIdx.y selects further column tiles.  B and C are
+// row-major in memory in every case.
 //
-// Column tiles: a lane group covers G*V columns; blockIdx.y selects the tile.
+// Memory-level parallelism: the hot loops fetch U entries' B segments back to back into registers
+// before the first multiply-add consumes them, so that every wave keeps U gathers in flight; row
+// bookkeeping (EB) happens while those loads are outstanding.
 //
 // No MFMA anywhere: every multiply-add consumes a freshly gathered B operand, there is no dense
 // tile to contract.
@@ -27,6 +31,7 @@ namespace daspmm {
 constexpr int kWave = 64;
 constexpr int kBlock = 256;                 // 4 waves
 constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kU = 8;                       // gathers in flight per lane
 
 // ------------------------------------------------------------------------------------------
 // small helpers
@@ -36,10 +41,8 @@ __device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&x)
     if constexpr (V == 4) {
         const float4 t = *reinterpret_cast<const float4*>(p);
         x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-    } else if constexpr (V == 2) {
-        const float2 t = *reinterpret_cast<const float2*>(p);
-        x[0] = t.x; x[1] = t.y;
     } else {
+        static_assert(V == 1, "V is 1 or 4");
         x[0] = *p;
     }
 }
@@ -48,8 +51,6 @@ template <int V>
 __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&x)[V]) {
     if constexpr (V == 4) {
         *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
-    } else if constexpr (V == 2) {
-        *reinterpret_cast<float2*>(p) = make_float2(x[0], x[1]);
     } else {
         *p = x[0];
     }
@@ -58,20 +59,55 @@ __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&x
 // Rows shared between workers are combined with hardware fp32 atomic adds (Sec. 4: "atomic_add"
 // for rows assigned to different workers); the return value is not used.
 template <int V>
-__device__ __forceinline__ void atomic_add_vec(float* __restrict__ p, const float (&x)[V]) {
-#pragma unroll
-    for (int v = 0; v < V; ++v) unsafeAtomicAdd(p + v, x[v]);
-}
-
-template <int V>
 __device__ __forceinline__ void emit_vec(float* __restrict__ p, const float (&x)[V], bool atomic) {
-    if (atomic) atomic_add_vec<V>(p, x); else store_vec<V>(p, x);
+    if (atomic) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) unsafeAtomicAdd(p + v, x[v]);
+    } else {
+        store_vec<V>(p, x);
+    }
 }
 
-template <int V>
-__device__ __forceinline__ void fma_vec(float (&acc)[V], float a, const float (&b)[V]) {
+// A lane's accumulators: NV vectors of V columns, vector i at column offset i*V from the lane's n0.
+template <int V, int NV>
+struct Acc {
+    float a[NV][V];
+    __device__ __forceinline__ void clear() {
 #pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] = fmaf(a, b[v], acc[v]);
+        for (int i = 0; i < NV; ++i)
+#pragma unroll
+            for (int v = 0; v < V; ++v) a[i][v] = 0.f;
+    }
+    // Branch-free gather of the lane's vectors of one B row (nvalid >= 1).  Vectors past nvalid
+    // re-read vector 0 (valid memory); their values are never written out.
+    __device__ __forceinline__ void load(const float* __restrict__ p, int nvalid) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) load_vec<V>(p + (i < nvalid ? i : 0) * V, a[i]);
+    }
+    __device__ __forceinline__ void fma(float s, const Acc& b) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+#pragma unroll
+            for (int v = 0; v < V; ++v) a[i][v] = fmaf(s, b.a[i][v], a[i][v]);
+    }
+    __device__ __forceinline__ void add(const Acc& b) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+#pragma unroll
+            for (int v = 0; v < V; ++v) a[i][v] += b.a[i][v];
+    }
+    __device__ __forceinline__ void emit(float* __restrict__ p, int nvalid, bool atomic) const {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            if (i < nvalid) emit_vec<V>(p + i * V, a[i], atomic);
+    }
+};
+
+// number of valid V-vectors of a lane whose first column is n0
+template <int V, int NV>
+__device__ __forceinline__ int valid_vectors(int n0, int N) {
+    const int left = (N - n0 + V - 1) / V;          // V == 4 implies N % 4 == 0
+    return left < 0 ? 0 : (left > NV ? NV : left);
 }
 
 // Orders LDS traffic of the lanes of one wave: the LDS unit serves one wave's requests in issue
@@ -92,64 +128,93 @@ __device__ __forceinline__ int row_of_entry(const int* __restrict__ rowptr, int 
     return lo;
 }
 
+// entries a lane group stages per batch
+template <int G> struct StageBatch { static constexpr int value = G < kU ? kU : G; };
+
+template <int U> struct Count { static constexpr int value = U; };
+
+// Calls f(Count<UU>, t) for t covering [0, cnt) in blocks of UMAX, then 4, 2, 1 entries, so that
+// every block is straight-line code of a compile-time size: its gathers carry no predicates and
+// are all in flight before the first one is consumed.
+template <int UMAX, class F>
+__device__ __forceinline__ void for_blocks(int cnt, F&& f) {
+    int t = 0;
+    for (; t + UMAX <= cnt; t += UMAX) f(Count<UMAX>{}, t);
+    if constexpr (UMAX > 4) { if (t + 4 <= cnt) { f(Count<4>{}, t); t += 4; } }
+    if constexpr (UMAX > 2) { if (t + 2 <= cnt) { f(Count<2>{}, t); t += 2; } }
+    if constexpr (UMAX > 1) { if (t < cnt) f(Count<1>{}, t); }
+}
+
 // ------------------------------------------------------------------------------------------
 // RB + SR : a lane group owns a row and adds its products one after another
-// (Sec. 3.2 design M1, Sec. 3.4 design K1).  The group's G lanes load G stored entries with one
-// coalesced request and pass them round through LDS so that every entry is fetched once and
-// reused for all columns of the tile (the sparse-element cache of Sec. 4).
+// (Sec. 3.2 design M1, Sec. 3.4 design K1).  For G > 1 the group's lanes load a batch of stored
+// entries with coalesced requests and pass them round through LDS, so that every entry is fetched
+// once and reused for all columns of the tile (the sparse-element cache of Sec. 4).
 // ------------------------------------------------------------------------------------------
-template <int V, int G>
+template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C)
 {
     constexpr int RPW = kWave / G;                       // rows per wave
-    __shared__ int2 stage[G > 1 ? kBlock : 1];
+    constexpr int SB = StageBatch<G>::value;
+    constexpr int UL = G == 1 ? kU / NV : kU;            // entries whose gathers are issued together
+    __shared__ int2 stage[G > 1 ? kWavesPerBlock * RPW * SB : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int g = lane / G, j = lane % G;
     const long row = ((long)blockIdx.x * kWavesPerBlock + wave) * RPW + g;
-    const int n0 = (blockIdx.y * G + j) * V;
-    const bool nok = n0 < N;
+    const int n0 = (blockIdx.y * G + j) * V * NV;
+    const int nvec = valid_vectors<V, NV>(n0, N);
     int start = 0, end = 0;
     if (row < m) { start = rowptr[row]; end = rowptr[row + 1]; }
-    float acc[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] = 0.f;
+    Acc<V, NV> acc;
+    acc.clear();
     const float* __restrict__ Bn = B + n0;
 
     if constexpr (G == 1) {
-        if (nok) {
-#pragma unroll 4
-            for (int p = start; p < end; ++p) {
-                const int c = colind[p];
-                const float a = vals[p];
-                float b[V];
-                load_vec<V>(Bn + (long)c * N, b);
-                fma_vec<V>(acc, a, b);
-            }
+        if (nvec > 0) {
+            for_blocks<UL>(end - start, [&](auto uc, int t) {
+                constexpr int UU = decltype(uc)::value;
+                const int p0 = start + t;
+                int c[UU];
+                float a[UU];
+                Acc<V, NV> b[UU];
+#pragma unroll
+                for (int u = 0; u < UU; ++u) { c[u] = colind[p0 + u]; a[u] = vals[p0 + u]; }
+#pragma unroll
+                for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)c[u] * N, nvec);
+#pragma unroll
+                for (int u = 0; u < UU; ++u) acc.fma(a[u], b[u]);
+            });
         }
     } else {
-        int2* st = stage + wave * kWave + g * G;
-        for (int p0 = start; p0 < end; p0 += G) {
-            const int p = p0 + j;
-            int2 e = make_int2(0, 0);
-            if (p < end) { e.x = colind[p]; e.y = __float_as_int(vals[p]); }
-            st[j] = e;
+        int2* st = stage + (wave * RPW + g) * SB;
+        for (int p0 = start; p0 < end; p0 += SB) {
+#pragma unroll
+            for (int i = j; i < SB; i += G) {
+                const int p = p0 + i;
+                int2 e = make_int2(0, 0);
+                if (p < end) { e.x = colind[p]; e.y = __float_as_int(vals[p]); }
+                st[i] = e;
+            }
             wave_lds_sync();
-            const int cnt = min(G, end - p0);
-            if (nok) {
-#pragma unroll 4
-                for (int t = 0; t < cnt; ++t) {
-                    const int2 ee = st[t];
-                    float b[V];
-                    load_vec<V>(Bn + (long)ee.x * N, b);
-                    fma_vec<V>(acc, __int_as_float(ee.y), b);
-                }
+            if (nvec > 0) {
+                for_blocks<UL>(min(SB, end - p0), [&](auto uc, int t) {
+                    constexpr int UU = decltype(uc)::value;
+                    int2 e[UU];
+                    Acc<V, NV> b[UU];
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) e[u] = st[t + u];
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * N, nvec);
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) acc.fma(__int_as_float(e[u].y), b[u]);
+                });
             }
             wave_lds_sync();
         }
     }
-    if (row < m && nok) store_vec<V>(C + row * N + n0, acc);
+    if (row < m && nvec > 0) acc.emit(C + row * N + n0, nvec, false);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -157,34 +222,49 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
 // (times G lanes along n).  Rows longer than S are walked with a for-loop (technique 1 of Sec. 4),
 // lanes load V consecutive columns at once (technique 2), the wave's entries are fetched once and
 // shared through LDS (technique 3), and the slots are combined by a reduction tree (Sec. 3.4 K2).
+// In a batch of 64 staged entries slot s takes entries s, s+S, s+2S, ...
 // ------------------------------------------------------------------------------------------
-template <int V, int G>
+template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C)
 {
     constexpr int S = kWave / G;
+    constexpr int UL = G == 1 ? (NV > 2 ? 2 : 4) : (G < kU ? G : kU);
     __shared__ int2 stage[G > 1 ? kBlock : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s = lane / G, j = lane % G;
     const long row = (long)blockIdx.x * kWavesPerBlock + wave;
     if (row >= m) return;                                 // whole wave leaves together
-    const int n0 = (blockIdx.y * G + j) * V;
-    const bool nok = n0 < N;
+    const int n0 = (blockIdx.y * G + j) * V * NV;
+    const int nvec = valid_vectors<V, NV>(n0, N);
     const int start = rowptr[row], end = rowptr[row + 1];
-    float acc[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) acc[v] = 0.f;
+    Acc<V, NV> acc;
+    acc.clear();
     const float* __restrict__ Bn = B + n0;
 
     if constexpr (G == 1) {
-        if (nok) {
-            for (int p = start + lane; p < end; p += kWave) {
-                const int c = colind[p];
-                const float a = vals[p];
-                float b[V];
-                load_vec<V>(Bn + (long)c * N, b);
-                fma_vec<V>(acc, a, b);
+        if (nvec > 0) {
+            // steps in which all 64 lanes hold an entry, then one ragged step
+            const int len = end - start;
+            for_blocks<UL>(len / kWave, [&](auto uc, int t) {
+                constexpr int UU = decltype(uc)::value;
+                const int p0 = start + t * kWave + lane;
+                int c[UU];
+                float a[UU];
+                Acc<V, NV> b[UU];
+#pragma unroll
+                for (int u = 0; u < UU; ++u) { c[u] = colind[p0 + u * kWave]; a[u] = vals[p0 + u * kWave]; }
+#pragma unroll
+                for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)c[u] * N, nvec);
+#pragma unroll
+                for (int u = 0; u < UU; ++u) acc.fma(a[u], b[u]);
+            });
+            const int p = start + (len / kWave) * kWave + lane;
+            if (p < end) {
+                Acc<V, NV> b;
+                b.load(Bn + (long)colind[p] * N, nvec);
+                acc.fma(vals[p], b);
             }
         }
     } else {
@@ -196,13 +276,24 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
             st[lane] = e;
             wave_lds_sync();
             const int cnt = min(kWave, end - p0);
-            if (nok) {
-#pragma unroll 2
-                for (int t = s; t < cnt; t += S) {
+            if (nvec > 0) {
+                for_blocks<UL>(cnt / S, [&](auto uc, int t) {
+                    constexpr int UU = decltype(uc)::value;
+                    int2 ee[UU];
+                    Acc<V, NV> b[UU];
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) ee[u] = st[(t + u) * S + s];
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)ee[u].x * N, nvec);
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) acc.fma(__int_as_float(ee[u].y), b[u]);
+                });
+                const int t = (cnt / S) * S + s;              // ragged last step
+                if (t < cnt) {
                     const int2 ee = st[t];
-                    float b[V];
-                    load_vec<V>(Bn + (long)ee.x * N, b);
-                    fma_vec<V>(acc, __int_as_float(ee.y), b);
+                    Acc<V, NV> b;
+                    b.load(Bn + (long)ee.x * N, nvec);
+                    acc.fma(__int_as_float(ee.y), b);
                 }
             }
             wave_lds_sync();
@@ -212,9 +303,11 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 #pragma unroll
     for (int d = kWave / 2; d >= G; d >>= 1) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) acc[v] += __shfl_down(acc[v], d, kWave);
+        for (int i = 0; i < NV; ++i)
+#pragma unroll
+            for (int v = 0; v < V; ++v) acc.a[i][v] += __shfl_down(acc.a[i][v], d, kWave);
     }
-    if (s == 0 && nok) store_vec<V>(C + row * N + n0, acc);
+    if (s == 0 && nvec > 0) acc.emit(C + row * N + n0, nvec, false);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -223,24 +316,32 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 // store; a row that straddles a chunk boundary receives atomic additions from several workers and
 // must start from zero; a row without entries is touched by no worker.  This pass zeroes exactly
 // those two kinds of rows so that C needs no full memset.  `chunk` is the number of entries per
-// worker of the product kernel that follows.
+// worker of the product kernel that follows.  A wave inspects 64 rows (one per lane) and then
+// clears the flagged ones together, one row at a time, with full-width stores.
 // ------------------------------------------------------------------------------------------
-template <int V, int G>
+template <int V>
 __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
     int m, int N, const int* __restrict__ rowptr, float* __restrict__ C, int chunk)
 {
-    constexpr int RPW = kWave / G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int g = lane / G, j = lane % G;
-    const long row = ((long)blockIdx.x * kWavesPerBlock + wave) * RPW + g;
-    if (row >= m) return;
-    const int start = rowptr[row], end = rowptr[row + 1];
-    const bool need = (end == start) || (start / chunk != (end - 1) / chunk);
-    if (!need) return;
+    const long base = ((long)blockIdx.x * kWavesPerBlock + wave) * kWave;
+    if (base >= m) return;
+    const long row = base + lane;
+    bool need = false;
+    if (row < m) {
+        const int start = rowptr[row], end = rowptr[row + 1];
+        need = (end == start) || (start / chunk != (end - 1) / chunk);
+    }
+    unsigned long long mask = __ballot(need);
     float z[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) z[v] = 0.f;
-    for (int n0 = j * V; n0 < N; n0 += G * V) store_vec<V>(C + row * N + n0, z);
+    while (mask) {
+        const int r = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        float* __restrict__ crow = C + (base + r) * N;
+        for (int n0 = lane * V; n0 < N; n0 += kWave * V) store_vec<V>(crow + n0, z);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -252,23 +353,25 @@ __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
 // named there).  Workers stride over the chunks so that the grid size does not depend on nnz,
 // which only the device knows.
 // ------------------------------------------------------------------------------------------
-template <int V, int G>
+template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk)
 {
     constexpr int GPW = kWave / G;                        // workers per wave
-    __shared__ int2 stage[G > 1 ? kBlock : 1];
+    constexpr int SB = StageBatch<G>::value;
+    constexpr int UL = G == 1 ? kU / NV : kU;             // entries whose gathers are issued together
+    __shared__ int2 stage[G > 1 ? kWavesPerBlock * GPW * SB : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int g = lane / G, j = lane % G;
-    const int n0 = (blockIdx.y * G + j) * V;
-    const bool nok = n0 < N;
+    const int n0 = (blockIdx.y * G + j) * V * NV;
+    const int nvec = valid_vectors<V, NV>(n0, N);
     const float* __restrict__ Bn = B + n0;
     float* __restrict__ Cn = C + n0;
     const int nnz = rowptr[m];
     const long nworkers = (long)gridDim.x * kWavesPerBlock * GPW;
     const long worker = ((long)blockIdx.x * kWavesPerBlock + wave) * GPW + g;
-    int2* st = stage + (G > 1 ? wave * kWave + g * G : 0);
+    int2* st = stage + (G > 1 ? (wave * GPW + g) * SB : 0);
 
     for (long c0l = worker * chunk; c0l < nnz; c0l += nworkers * chunk) {
         const int c0 = (int)c0l;
@@ -276,46 +379,51 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
         int row = row_of_entry(rowptr, 0, m - 1, c0);
         int row_end = rowptr[row + 1];
         bool shared_with_prev = rowptr[row] < c0;          // only the chunk's first row can be
-        float acc[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) acc[v] = 0.f;
+        Acc<V, NV> acc;
+        acc.clear();
 
-        for (int q0 = c0; q0 < c1; q0 += G) {
+        for (int q0 = c0; q0 < c1; q0 += SB) {
             if constexpr (G > 1) {
-                const int q = q0 + j;
-                int2 e = make_int2(0, 0);
-                if (q < c1) { e.x = colind[q]; e.y = __float_as_int(vals[q]); }
-                st[j] = e;
+#pragma unroll
+                for (int i = j; i < SB; i += G) {
+                    const int q = q0 + i;
+                    int2 e = make_int2(0, 0);
+                    if (q < c1) { e.x = colind[q]; e.y = __float_as_int(vals[q]); }
+                    st[i] = e;
+                }
                 wave_lds_sync();
             }
-            const int cnt = min(G, c1 - q0);
-            int t = 0;
-            while (t < cnt) {
-                const int stop = min(cnt, row_end - q0);
-                for (; t < stop; ++t) {
-                    int2 ee;
-                    if constexpr (G > 1) ee = st[t];
-                    else ee = make_int2(colind[q0], __float_as_int(vals[q0]));
-                    if (nok) {
-                        float b[V];
-                        load_vec<V>(Bn + (long)ee.x * N, b);
-                        fma_vec<V>(acc, __int_as_float(ee.y), b);
-                    }
-                }
-                if (q0 + t == row_end) {                   // the row is complete
-                    if (nok) emit_vec<V>(Cn + (long)row * N, acc, shared_with_prev);
+            for_blocks<UL>(min(SB, c1 - q0), [&](auto uc, int t) {
+                constexpr int UU = decltype(uc)::value;
+                int2 e[UU];
+                Acc<V, NV> b[UU];
 #pragma unroll
-                    for (int v = 0; v < V; ++v) acc[v] = 0.f;
-                    shared_with_prev = false;
-                    if (q0 + t < c1) {
-                        do { ++row; row_end = rowptr[row + 1]; } while (row_end <= q0 + t);
+                for (int u = 0; u < UU; ++u) {
+                    if constexpr (G > 1) e[u] = st[t + u];
+                    else e[u] = make_int2(colind[q0 + t + u], __float_as_int(vals[q0 + t + u]));
+                }
+                if (nvec > 0) {
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * N, nvec);
+                }
+#pragma unroll
+                for (int u = 0; u < UU; ++u) {
+                    if (nvec > 0) acc.fma(__int_as_float(e[u].y), b[u]);
+                    const int next = q0 + t + u + 1;
+                    if (next == row_end) {                     // the row is complete
+                        if (nvec > 0) acc.emit(Cn + (long)row * N, nvec, shared_with_prev);
+                        acc.clear();
+                        shared_with_prev = false;
+                        if (next < c1) {
+                            do { ++row; row_end = rowptr[row + 1]; } while (row_end <= next);
+                        }
                     }
                 }
-            }
+            });
             if constexpr (G > 1) wave_lds_sync();
         }
-        if (row_end > c1 && nok)                           // last row continues in the next chunk
-            emit_vec<V>(Cn + (long)row * N, acc, true);
+        if (row_end > c1 && nvec > 0)                      // last row continues in the next chunk
+            acc.emit(Cn + (long)row * N, nvec, true);
     }
 }
 
@@ -331,17 +439,18 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
 // Rows that are complete inside the chunk get one plain store; only the first and last row of a
 // chunk, when shared with the neighbouring chunks, are combined with atomic adds.
 // ------------------------------------------------------------------------------------------
-template <int V, int G>
+template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk)
 {
     constexpr int S = kWave / G;
+    constexpr int UU = G < kU ? G : kU;                   // steps whose gathers are issued together
     __shared__ int4 stage[G > 1 ? kBlock : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s = lane / G, j = lane % G;
-    const int n0 = (blockIdx.y * G + j) * V;
-    const bool nok = n0 < N;
+    const int n0 = (blockIdx.y * G + j) * V * NV;
+    const int nvec = valid_vectors<V, NV>(n0, N);
     const float* __restrict__ Bn = B + n0;
     float* __restrict__ Cn = C + n0;
     const int nnz = rowptr[m];
@@ -354,9 +463,8 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
         const int c1 = (int)min(c0l + chunk, (long)nnz);
         const int row_lo = row_of_entry(rowptr, 0, m - 1, c0);
         const int row_hi = row_of_entry(rowptr, row_lo, m - 1, c1 - 1);
-        float carry[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) carry[v] = 0.f;
+        Acc<V, NV> carry;
+        carry.clear();
         int carry_row = -1;
         bool carry_started = false;
 
@@ -375,63 +483,77 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
             if constexpr (G > 1) { st[lane] = mine; wave_lds_sync(); }
             const int cnt = min(kWave, c1 - q0);
 
-            for (int t0 = 0; t0 < cnt; t0 += S) {
-                int4 e;
-                if constexpr (G > 1) e = st[t0 + s]; else e = mine;
-                const bool evalid = t0 + s < cnt;
-                const int er = e.z;
-                float x[V];
+            for (int tb = 0; tb * S < cnt; tb += UU) {
+                int4 e[UU];
+                Acc<V, NV> x[UU];
 #pragma unroll
-                for (int v = 0; v < V; ++v) x[v] = 0.f;
-                if (evalid && nok) {
-                    float b[V];
-                    load_vec<V>(Bn + (long)e.x * N, b);
-                    const float a = __int_as_float(e.y);
-#pragma unroll
-                    for (int v = 0; v < V; ++v) x[v] = a * b[v];
+                for (int u = 0; u < UU; ++u) {
+                    if constexpr (G > 1) e[u] = st[((tb + u) * S + s) & (kWave - 1)]; else e[u] = mine;
+                    if ((tb + u) * S + s >= cnt) e[u].z = -1;
                 }
-                // conditional reduction network over the slots
+                // branch-free gathers: slots past the end of the chunk hold column 0
+                if (nvec > 0) {
 #pragma unroll
-                for (int d = 1; d < S; d <<= 1) {
-                    const int orow = __shfl_down(er, d * G, kWave);
-                    const bool take = (s + d < S) && (orow == er);
+                    for (int u = 0; u < UU; ++u) x[u].load(Bn + (long)e[u].x * N, nvec);
+                }
 #pragma unroll
-                    for (int v = 0; v < V; ++v) {
-                        const float ox = __shfl_down(x[v], d * G, kWave);
-                        if (take) x[v] += ox;
+                for (int u = 0; u < UU; ++u) {
+                    const int t0 = (tb + u) * S;                       // first entry of this step
+                    if (t0 >= cnt) break;                              // wave-uniform
+                    const int er = e[u].z;
+                    const bool evalid = er >= 0;
+                    const float a = __int_as_float(e[u].y);
+#pragma unroll
+                    for (int i = 0; i < NV; ++i)
+#pragma unroll
+                        for (int v = 0; v < V; ++v)
+                            x[u].a[i][v] = (evalid && nvec > 0) ? a * x[u].a[i][v] : 0.f;
+                    // conditional reduction network over the slots
+#pragma unroll
+                    for (int d = 1; d < S; d <<= 1) {
+                        const int orow = __shfl_down(er, d * G, kWave);
+                        const bool take = (s + d < S) && (orow == er);
+#pragma unroll
+                        for (int i = 0; i < NV; ++i)
+#pragma unroll
+                            for (int v = 0; v < V; ++v) {
+                                const float ox = __shfl_down(x[u].a[i][v], d * G, kWave);
+                                if (take) x[u].a[i][v] += ox;
+                            }
                     }
-                }
-                const int prow = __shfl_up(er, G, kWave);
-                const bool head = evalid && (s == 0 || prow != er);
-                const int nv = min(S, cnt - t0);                       // valid slots in this step
-                const int tail_lane = (nv - 1) * G;
-                const int tail_row = __shfl(er, tail_lane, kWave);
-                const bool tail_ended = (__shfl(e.w, tail_lane, kWave) & 2) != 0;
-                bool started = (e.w & 1) != 0;
-                if (s == 0 && carry_row == er) {                        // continue the carried run
+                    const int prow = __shfl_up(er, G, kWave);
+                    const bool head = evalid && (s == 0 || prow != er);
+                    const int nv = min(S, cnt - t0);                   // valid slots in this step
+                    const int tail_lane = (nv - 1) * G;
+                    const int tail_row = __shfl(er, tail_lane, kWave);
+                    const bool tail_ended = (__shfl(e[u].w, tail_lane, kWave) & 2) != 0;
+                    bool started = (e[u].w & 1) != 0;
+                    if (s == 0 && carry_row == er) {                    // continue the carried run
+                        x[u].add(carry);
+                        started = carry_started;
+                    }
+                    const bool in_tail_run = evalid && er == tail_row;
+                    if (head && nvec > 0 && (!in_tail_run || tail_ended))
+                        x[u].emit(Cn + (long)er * N, nvec, !started);
+                    if (!tail_ended) {
+                        // leftmost slot of the tail run -> every slot keeps a copy of the carry
+                        const unsigned long long mask = __ballot(in_tail_run);
+                        const int src = (__ffsll((long long)mask) - 1) / G * G + j;
 #pragma unroll
-                    for (int v = 0; v < V; ++v) x[v] += carry[v];
-                    started = carry_started;
-                }
-                const bool in_tail_run = evalid && er == tail_row;
-                if (head && nok && (!in_tail_run || tail_ended))
-                    emit_vec<V>(Cn + (long)er * N, x, !started);
-                if (!tail_ended) {
-                    // leftmost slot of the tail run -> every slot keeps a copy of the carry
-                    const unsigned long long mask = __ballot(in_tail_run);
-                    const int src = (__ffsll((long long)mask) - 1) / G * G + j;
+                        for (int i = 0; i < NV; ++i)
 #pragma unroll
-                    for (int v = 0; v < V; ++v) carry[v] = __shfl(x[v], src, kWave);
-                    carry_started = __shfl((int)started, src, kWave) != 0;
-                    carry_row = tail_row;
-                } else {
-                    carry_row = -1;
+                            for (int v = 0; v < V; ++v) carry.a[i][v] = __shfl(x[u].a[i][v], src, kWave);
+                        carry_started = __shfl((int)started, src, kWave) != 0;
+                        carry_row = tail_row;
+                    } else {
+                        carry_row = -1;
+                    }
                 }
             }
             if constexpr (G > 1) wave_lds_sync();
         }
-        if (carry_row >= 0 && s == 0 && nok)                 // row continues in the next chunk
-            emit_vec<V>(Cn + (long)carry_row * N, carry, true);
+        if (carry_row >= 0 && s == 0 && nvec > 0)            // row continues in the next chunk
+            carry.emit(Cn + (long)carry_row * N, nvec, true);
     }
 }
 
