@@ -53,6 +53,25 @@ def make_workload(name: str, N: int):
     return a, B, desc
 
 
+def measured_traffic(workload: str, N: int, algo_name: str):
+    """HBM bytes per da_spmm call from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy kernel's reading), or None when no
+    summary exists for this workload / algorithm."""
+    path = os.path.join(ROOT, "profiles", f"da_spmm_{workload}_N{N}_hbm_traffic.txt")
+    try:
+        vals = {}
+        for line in open(path):
+            if "=" in line and line.split("=")[0].strip() in ("ALGO", "FETCH_KIB_PER_CALL_SCALED",
+                                                              "WRITE_KIB_PER_CALL_SCALED"):
+                k, v = line.split("=", 1)
+                vals[k.strip()] = v.strip()
+        if vals.get("ALGO") != algo_name:
+            return None
+        return int((float(vals["FETCH_KIB_PER_CALL_SCALED"]) + float(vals["WRITE_KIB_PER_CALL_SCALED"])) * 1024)
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def compulsory_bytes(m, k, nnz, N):
     return 4 * (m + 1) + 8 * nnz + 4 * k * N + 4 * m * N
 
@@ -150,7 +169,8 @@ def main():
                    "N": N, "algo": da.ALGO_NAMES[chosen], "selected_by": "da_spmm_select" if fixed is None else "fixed",
                    "copies_rotated": len(copies)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic(args.workload, N, da.ALGO_NAMES[chosen]),
                      "kernel": f"da_spmm({da.ALGO_NAMES[chosen]}) incl. EB zero pre-pass",
                      "algorithmic_bytes_per_launch": cbytes},
         "features_ms_once_per_matrix": round(feat_ms, 3), "select_us_per_call": round(select_us, 3),

@@ -102,6 +102,10 @@ int da_spmm_select(const da_features *f);
  * Extract the selector's input characteristics (Sec. 5.1, Table 2) from the row pointers with one
  * device reduction.  rowptr is a device pointer (int32[m+1]); `out` is a HOST pointer.  Blocks
  * until the result is on the host (synchronises `stream`).  m == 0 gives all-zero features.
+ * Side effect: the library remembers nnz for this (rowptr, m) pair in a small host table and
+ * later da_spmm calls on the same matrix use it to size the grids of the EB algorithms (a
+ * missing or stale entry only costs speed: EB kernels read nnz on the device and cover every
+ * stored entry whatever the grid size).
  */
 int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, da_features *out);
 

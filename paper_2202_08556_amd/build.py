@@ -40,5 +40,20 @@ def build_hip(verbose: bool = False) -> str:
     return LIB
 
 
+CALIB = os.path.join(PKG, "calib_copy")
+
+
+def build_calib(verbose: bool = False) -> str:
+    """Standalone copy kernel used to calibrate rocprofv3's HBM traffic counters."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-o", CALIB, os.path.join(CSRC, "calib_copy.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    return CALIB
+
+
 if __name__ == "__main__":
     print(build_hip(verbose=True))
+    print(build_calib(verbose=True))

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 namespace {
 
@@ -63,6 +64,7 @@ enum Family { RB_SR, RB_PR, EB_SR, EB_PR };
 // the number of stored entries per worker.
 struct Geometry {
     int V, G, NV, chunk;
+    bool pin;   // pin column tiles to XCDs when the tile count is 2, 4 or 8
 };
 
 constexpr int kMaxGridY = 65535;
@@ -83,7 +85,7 @@ bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const void* C, Geometry* out) {
     const uintptr_t addr = reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C);
     const bool vec4_ok = (N % 4 == 0) && (addr % 16 == 0);
-    Geometry g{1, 1, 1, 0};
+    Geometry g{1, 1, 1, 0, false};
     if (cm) {
         g.V = vec4_ok ? 4 : 1;
         const long vecs = (N + g.V - 1) / g.V;
@@ -101,6 +103,7 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
         g.V = env_int("DA_SPMM_V", g.V);
         g.G = env_int("DA_SPMM_G", g.G);
         g.NV = env_int("DA_SPMM_NV", g.NV);
+        g.pin = env_int("DA_SPMM_PIN", g.pin ? 1 : 0) != 0;
         if ((g.V != 1 && g.V != 4) || (g.V == 4 && !vec4_ok) || !is_pow2(g.G) || g.G > kWave ||
             (pr && g.G > kMaxGroupPR) || (g.NV != 1 && g.NV != 2 && g.NV != 4) || (g.G > 1 && g.NV != 1))
             return fail(DA_ERR_UNSUPPORTED, "DA_SPMM_V/_G/_NV override is not a supported combination%s");
@@ -115,26 +118,54 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
     return DA_OK;
 }
 
+// nnz of matrices whose features were extracted, keyed by (rowptr address, m).  da_spmm uses it
+// only to size EB grids; EB kernels stride over all chunks whatever the grid size, so a stale or
+// missing hint costs speed, never correctness.
+struct NnzHint { const void* rowptr; int64_t m; int64_t nnz; };
+std::mutex g_hint_mu;
+NnzHint g_hints[16];
+int g_hint_next = 0;
+
+void remember_nnz(const void* rowptr, int64_t m, int64_t nnz) {
+    std::lock_guard<std::mutex> lk(g_hint_mu);
+    for (auto& h : g_hints)
+        if (h.rowptr == rowptr && h.m == m) { h.nnz = nnz; return; }
+    g_hints[g_hint_next] = NnzHint{rowptr, m, nnz};
+    g_hint_next = (g_hint_next + 1) % 16;
+}
+
+int64_t lookup_nnz(const void* rowptr, int64_t m) {
+    std::lock_guard<std::mutex> lk(g_hint_mu);
+    for (const auto& h : g_hints)
+        if (h.rowptr == rowptr && h.m == m) return h.nnz;
+    return -1;
+}
+
 template <int V, int G, int NV>
-int launch(Family fam, const Problem& p, int chunk) {
+int launch(Family fam, const Problem& p, const Geometry& geo) {
+    const int chunk = geo.chunk;
     const long tile_cols = (long)G * V * NV;
     const long tiles_l = (p.N + tile_cols - 1) / tile_cols;
     if (tiles_l > kMaxGridY) return fail(DA_ERR_UNSUPPORTED, "N needs more than 65535 column tiles%s");
     const unsigned tiles = (unsigned)tiles_l;
+    const int pin = (geo.pin && (tiles == 2 || tiles == 4 || tiles == 8)) ? (int)tiles : 0;
+    // grid for `bx` blocks per column tile
+    auto grid_for = [&](long bx) {
+        if (pin) { const long per = 8 / pin; return dim3((unsigned)(8 * ((bx + per - 1) / per)), 1); }
+        return dim3((unsigned)bx, tiles);
+    };
     const dim3 block(kBlock);
     switch (fam) {
     case RB_SR: {
         const long rows_per_block = (long)kWavesPerBlock * (kWave / G);
-        const dim3 grid((unsigned)((p.m + rows_per_block - 1) / rows_per_block), tiles);
-        hipLaunchKernelGGL((rb_sr_kernel<V, G, NV>), grid, block, 0, p.stream,
-                           p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C);
+        hipLaunchKernelGGL((rb_sr_kernel<V, G, NV>), grid_for((p.m + rows_per_block - 1) / rows_per_block),
+                           block, 0, p.stream, p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, pin);
         break;
     }
     case RB_PR: {
         if constexpr (G <= kMaxGroupPR) {
-            const dim3 grid((unsigned)((p.m + kWavesPerBlock - 1) / kWavesPerBlock), tiles);
-            hipLaunchKernelGGL((rb_pr_kernel<V, G, NV>), grid, block, 0, p.stream,
-                               p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C);
+            hipLaunchKernelGGL((rb_pr_kernel<V, G, NV>), grid_for((p.m + kWavesPerBlock - 1) / kWavesPerBlock),
+                               block, 0, p.stream, p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, pin);
         }
         break;
     }
@@ -143,25 +174,33 @@ int launch(Family fam, const Problem& p, int chunk) {
         // entries per block and pass: a lane group (SR) or a whole wave (PR) owns `chunk` entries
         const long entries_per_block = fam == EB_SR ? (long)chunk * kWavesPerBlock * (kWave / G)
                                                     : (long)chunk * kWavesPerBlock;
-        // nnz is known only on the device; size the grid for a full machine, bounded by what the
-        // matrix could hold at most
-        long max_nnz = (long)p.m * (p.k < 1 ? 1 : p.k);
-        if (max_nnz > 0x7fffffffL) max_nnz = 0x7fffffffL;
-        long blocks = (max_nnz + entries_per_block - 1) / entries_per_block;
-        const long full = (long)cu_count() * 8;
-        if (blocks > full) blocks = full;
+        // One chunk per worker when nnz is known from an earlier da_spmm_features call (the
+        // hardware dispatcher then balances the blocks); otherwise nnz is known only on the
+        // device and the grid is sized for a few waves of blocks over the whole machine, bounded
+        // by what the matrix could hold at most.
+        long blocks;
+        const int64_t known = lookup_nnz(p.rowptr, p.m);
+        if (known >= 0) {
+            blocks = (known + entries_per_block - 1) / entries_per_block;
+            if (blocks > (1L << 20)) blocks = 1L << 20;
+        } else {
+            long max_nnz = (long)p.m * (p.k < 1 ? 1 : p.k);
+            if (max_nnz > 0x7fffffffL) max_nnz = 0x7fffffffL;
+            blocks = (max_nnz + entries_per_block - 1) / entries_per_block;
+            const long full = (long)cu_count() * 8 * 4;
+            if (blocks > full) blocks = full;
+        }
         if (blocks < 1) blocks = 1;
         // pre-pass: zero the rows that receive atomic additions, and the rows without entries
         const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
         hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.rowptr, p.C, chunk);
-        const dim3 grid((unsigned)blocks, tiles);
         if (fam == EB_SR) {
-            hipLaunchKernelGGL((eb_sr_kernel<V, G, NV>), grid, block, 0, p.stream,
-                               p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk);
+            hipLaunchKernelGGL((eb_sr_kernel<V, G, NV>), grid_for(blocks), block, 0, p.stream,
+                               p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin);
         } else {
             if constexpr (G <= kMaxGroupPR)
-                hipLaunchKernelGGL((eb_pr_kernel<V, G, NV>), grid, block, 0, p.stream,
-                                   p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk);
+                hipLaunchKernelGGL((eb_pr_kernel<V, G, NV>), grid_for(blocks), block, 0, p.stream,
+                                   p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin);
         }
         break;
     }
@@ -175,18 +214,18 @@ template <int V>
 int dispatch_v(Family fam, const Geometry& g, const Problem& p) {
     if (g.G == 1) {
         switch (g.NV) {
-        case 1: return launch<V, 1, 1>(fam, p, g.chunk);
-        case 2: return launch<V, 1, 2>(fam, p, g.chunk);
-        case 4: return launch<V, 1, 4>(fam, p, g.chunk);
+        case 1: return launch<V, 1, 1>(fam, p, g);
+        case 2: return launch<V, 1, 2>(fam, p, g);
+        case 4: return launch<V, 1, 4>(fam, p, g);
         }
     } else if (g.NV == 1) {
         switch (g.G) {
-        case 2: return launch<V, 2, 1>(fam, p, g.chunk);
-        case 4: return launch<V, 4, 1>(fam, p, g.chunk);
-        case 8: return launch<V, 8, 1>(fam, p, g.chunk);
-        case 16: return launch<V, 16, 1>(fam, p, g.chunk);
-        case 32: return launch<V, 32, 1>(fam, p, g.chunk);
-        case 64: return launch<V, 64, 1>(fam, p, g.chunk);
+        case 2: return launch<V, 2, 1>(fam, p, g);
+        case 4: return launch<V, 4, 1>(fam, p, g);
+        case 8: return launch<V, 8, 1>(fam, p, g);
+        case 16: return launch<V, 16, 1>(fam, p, g);
+        case 32: return launch<V, 32, 1>(fam, p, g);
+        case 64: return launch<V, 64, 1>(fam, p, g);
         }
     }
     return fail(DA_ERR_UNSUPPORTED, "unsupported lane mapping%s");
@@ -261,6 +300,7 @@ int da_spmm_features(int64_t m, int64_t N, const int32_t* rowptr, void* stream, 
     const double var = (double)num / (md * md);
     out->rows = m;
     out->nnz = (int64_t)h[2];
+    remember_nnz(rowptr, m, out->nnz);
     out->row_nnz_mean = mean;
     out->row_nnz_std = std::sqrt(var);
     out->row_nnz_max = (double)h[1];

@@ -13,8 +13,8 @@
 //   V   consecutive columns a lane loads at once (the float2/float4 technique of Sec. 4): 1 or 4.
 //   NV  vectors of V columns a lane walks one after another (CM: the lane's own strip of columns;
 //       RM uses NV = 1).
-// A lane group covers G*V*NV columns; blockIdx.y selects further column tiles.  B and C are
-// row-major in memory in every case.
+// A lane group covers G*V*NV columns; further column tiles are further blocks (see block_map).
+// B and C are row-major in memory in every case.
 //
 // Memory-level parallelism: the hot loops fetch U entries' B segments back to back into registers
 // before the first multiply-add consumes them, so that every wave keeps U gathers in flight; row
@@ -47,12 +47,17 @@ __device__ __forceinline__ void load_vec(const float* __restrict__ p, float (&x)
     }
 }
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// C is written once and never read back by the kernels: its stores are marked non-temporal so
+// that they do not push B rows out of L2.
 template <int V>
 __device__ __forceinline__ void store_vec(float* __restrict__ p, const float (&x)[V]) {
     if constexpr (V == 4) {
-        *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+        floatx4 t = {x[0], x[1], x[2], x[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<floatx4*>(p));
     } else {
-        *p = x[0];
+        __builtin_nontemporal_store(x[0], p);
     }
 }
 
@@ -133,6 +138,25 @@ template <int G> struct StageBatch { static constexpr int value = G < kU ? kU : 
 
 template <int U> struct Count { static constexpr int value = U; };
 
+// Which column tile a block works on and its rank among the blocks of that tile.
+//   pin_tiles == 0: 2-D grid, blockIdx.y = tile.
+//   pin_tiles in {2,4,8}: 1-D grid whose size is a multiple of 8.  Consecutive workgroups go to
+//     consecutive XCDs (8 per device, each with its own L2), so tile = (blockIdx.x % 8) % pin_tiles
+//     keeps every XCD on one tile: its L2 then caches only that tile's slice of B.
+struct BlockMap { int tile; long bx; long nbx; };
+__device__ __forceinline__ BlockMap block_map(int pin_tiles) {
+    BlockMap b;
+    if (pin_tiles <= 0) {
+        b.tile = blockIdx.y; b.bx = blockIdx.x; b.nbx = gridDim.x;
+    } else {
+        const int xcd = blockIdx.x & 7, per = 8 / pin_tiles;
+        b.tile = xcd % pin_tiles;
+        b.bx = (long)(blockIdx.x >> 3) * per + xcd / pin_tiles;
+        b.nbx = (long)(gridDim.x >> 3) * per;
+    }
+    return b;
+}
+
 // Calls f(Count<UU>, t) for t covering [0, cnt) in blocks of UMAX, then 4, 2, 1 entries, so that
 // every block is straight-line code of a compile-time size: its gathers carry no predicates and
 // are all in flight before the first one is consumed.
@@ -154,7 +178,7 @@ __device__ __forceinline__ void for_blocks(int cnt, F&& f) {
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
-    const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C)
+    const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int pin_tiles)
 {
     constexpr int RPW = kWave / G;                       // rows per wave
     constexpr int SB = StageBatch<G>::value;
@@ -162,8 +186,9 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
     __shared__ int2 stage[G > 1 ? kWavesPerBlock * RPW * SB : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int g = lane / G, j = lane % G;
-    const long row = ((long)blockIdx.x * kWavesPerBlock + wave) * RPW + g;
-    const int n0 = (blockIdx.y * G + j) * V * NV;
+    const BlockMap bm = block_map(pin_tiles);
+    const long row = (bm.bx * kWavesPerBlock + wave) * RPW + g;
+    const int n0 = (bm.tile * G + j) * V * NV;
     const int nvec = valid_vectors<V, NV>(n0, N);
     int start = 0, end = 0;
     if (row < m) { start = rowptr[row]; end = rowptr[row + 1]; }
@@ -227,16 +252,17 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
-    const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C)
+    const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int pin_tiles)
 {
     constexpr int S = kWave / G;
     constexpr int UL = G == 1 ? (NV > 2 ? 2 : 4) : (G < kU ? G : kU);
     __shared__ int2 stage[G > 1 ? kBlock : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s = lane / G, j = lane % G;
-    const long row = (long)blockIdx.x * kWavesPerBlock + wave;
+    const BlockMap bm = block_map(pin_tiles);
+    const long row = bm.bx * kWavesPerBlock + wave;
     if (row >= m) return;                                 // whole wave leaves together
-    const int n0 = (blockIdx.y * G + j) * V * NV;
+    const int n0 = (bm.tile * G + j) * V * NV;
     const int nvec = valid_vectors<V, NV>(n0, N);
     const int start = rowptr[row], end = rowptr[row + 1];
     Acc<V, NV> acc;
@@ -356,7 +382,8 @@ __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
-    const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk)
+    const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
+    int pin_tiles)
 {
     constexpr int GPW = kWave / G;                        // workers per wave
     constexpr int SB = StageBatch<G>::value;
@@ -364,13 +391,14 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     __shared__ int2 stage[G > 1 ? kWavesPerBlock * GPW * SB : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int g = lane / G, j = lane % G;
-    const int n0 = (blockIdx.y * G + j) * V * NV;
+    const BlockMap bm = block_map(pin_tiles);
+    const int n0 = (bm.tile * G + j) * V * NV;
     const int nvec = valid_vectors<V, NV>(n0, N);
     const float* __restrict__ Bn = B + n0;
     float* __restrict__ Cn = C + n0;
     const int nnz = rowptr[m];
-    const long nworkers = (long)gridDim.x * kWavesPerBlock * GPW;
-    const long worker = ((long)blockIdx.x * kWavesPerBlock + wave) * GPW + g;
+    const long nworkers = bm.nbx * kWavesPerBlock * GPW;
+    const long worker = (bm.bx * kWavesPerBlock + wave) * GPW + g;
     int2* st = stage + (G > 1 ? (wave * GPW + g) * SB : 0);
 
     for (long c0l = worker * chunk; c0l < nnz; c0l += nworkers * chunk) {
@@ -442,20 +470,22 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
-    const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk)
+    const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
+    int pin_tiles)
 {
     constexpr int S = kWave / G;
     constexpr int UU = G < kU ? G : kU;                   // steps whose gathers are issued together
     __shared__ int4 stage[G > 1 ? kBlock : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s = lane / G, j = lane % G;
-    const int n0 = (blockIdx.y * G + j) * V * NV;
+    const BlockMap bm = block_map(pin_tiles);
+    const int n0 = (bm.tile * G + j) * V * NV;
     const int nvec = valid_vectors<V, NV>(n0, N);
     const float* __restrict__ Bn = B + n0;
     float* __restrict__ Cn = C + n0;
     const int nnz = rowptr[m];
-    const long nwaves = (long)gridDim.x * kWavesPerBlock;
-    const long wave_id = (long)blockIdx.x * kWavesPerBlock + wave;
+    const long nwaves = bm.nbx * kWavesPerBlock;
+    const long wave_id = bm.bx * kWavesPerBlock + wave;
     int4* st = stage + (G > 1 ? wave * kWave : 0);
 
     for (long c0l = wave_id * chunk; c0l < nnz; c0l += nwaves * chunk) {
