@@ -117,6 +117,8 @@ def main():
     t1 = time.perf_counter()
     feats = da.da_spmm_features(a.m, N, copies[0]["rp"])
     feat_ms = (time.perf_counter() - t1) * 1e3
+    for c in copies[1:]:                      # every rotated copy is a matrix of its own
+        da.da_spmm_features(a.m, N, c["rp"])
     t1 = time.perf_counter()
     for _ in range(1000):
         sel = da.da_spmm_select(feats)

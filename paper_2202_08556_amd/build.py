@@ -41,17 +41,25 @@ def build_hip(verbose: bool = False) -> str:
 
 
 CALIB = os.path.join(PKG, "calib_copy")
+CEILINGS = os.path.join(PKG, "ceilings")
 
 
-def build_calib(verbose: bool = False) -> str:
-    """Standalone copy kernel used to calibrate rocprofv3's HBM traffic counters."""
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-o", CALIB, os.path.join(CSRC, "calib_copy.hip")]
+def _build_tool(src: str, exe: str, verbose: bool) -> str:
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-munsafe-fp-atomics",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-o", exe, os.path.join(CSRC, src)]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
-    return CALIB
+    return exe
+
+
+def build_calib(verbose: bool = False) -> str:
+    """Stand-alone measurement tools: the copy kernel that calibrates rocprofv3's HBM traffic
+    counters, and the stream / gather / atomics ceilings of the memory system."""
+    _build_tool("calib_copy.hip", CALIB, verbose)
+    return _build_tool("ceilings.hip", CEILINGS, verbose)
 
 
 if __name__ == "__main__":

@@ -78,11 +78,35 @@ int env_int(const char* name, int fallback) {
 
 bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
+// nnz of matrices whose features were extracted, keyed by (rowptr address, m).  da_spmm uses it
+// only to size EB grids; EB kernels stride over all chunks whatever the grid size, so a stale or
+// missing hint costs speed, never correctness.
+struct NnzHint { const void* rowptr; int64_t m; int64_t nnz; };
+std::mutex g_hint_mu;
+NnzHint g_hints[16];
+int g_hint_next = 0;
+
+void remember_nnz(const void* rowptr, int64_t m, int64_t nnz) {
+    std::lock_guard<std::mutex> lk(g_hint_mu);
+    for (auto& h : g_hints)
+        if (h.rowptr == rowptr && h.m == m) { h.nnz = nnz; return; }
+    g_hints[g_hint_next] = NnzHint{rowptr, m, nnz};
+    g_hint_next = (g_hint_next + 1) % 16;
+}
+
+int64_t lookup_nnz(const void* rowptr, int64_t m) {
+    std::lock_guard<std::mutex> lk(g_hint_mu);
+    for (const auto& h : g_hints)
+        if (h.rowptr == rowptr && h.m == m) return h.nnz;
+    return -1;
+}
+
 // Default geometry per algorithm family and N.  Measured on MI355X: 16-byte and 4-byte gathers
 // run at full rate, 8-byte gathers at about half, and narrow rows (N < 32) gather fastest with one
 // column per lane.  Setting DA_SPMM_TUNE=1 lets DA_SPMM_V / _G / _NV / _CHUNK override the choice
 // (for tuning runs only; invalid combinations are rejected).
-int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const void* C, Geometry* out) {
+int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const void* C, int64_t known_nnz,
+                  Geometry* out) {
     const uintptr_t addr = reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C);
     const bool vec4_ok = (N % 4 == 0) && (addr % 16 == 0);
     Geometry g{1, 1, 1, 0, false};
@@ -111,34 +135,22 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
     if (eb) {
         if (pr) g.chunk = kEntriesPerWavePR;
         else g.chunk = g.G >= 8 ? 256 : (g.G == 4 ? 128 : 64);
+        if (known_nnz >= 0) {
+            // Small matrices: shrink the chunks until there are about two workers per hardware
+            // slot (8 waves on each of 4 SIMDs per CU), so that the chunk walk, which is a chain of
+            // dependent memory round trips, does not set the run time.
+            const long slots = (long)cu_count() * 32 * (pr ? 1 : kWave / g.G);
+            const int floor_ = pr ? 64 : 32;
+            long want = known_nnz / (2 * slots);
+            want = (want + 7) / 8 * 8;
+            if (want < floor_) want = floor_;
+            if (want < g.chunk) g.chunk = (int)want;
+        }
         if (tune) g.chunk = env_int("DA_SPMM_CHUNK", g.chunk);
         if (g.chunk < 8 || g.chunk > (1 << 20)) return fail(DA_ERR_UNSUPPORTED, "bad DA_SPMM_CHUNK%s");
     }
     *out = g;
     return DA_OK;
-}
-
-// nnz of matrices whose features were extracted, keyed by (rowptr address, m).  da_spmm uses it
-// only to size EB grids; EB kernels stride over all chunks whatever the grid size, so a stale or
-// missing hint costs speed, never correctness.
-struct NnzHint { const void* rowptr; int64_t m; int64_t nnz; };
-std::mutex g_hint_mu;
-NnzHint g_hints[16];
-int g_hint_next = 0;
-
-void remember_nnz(const void* rowptr, int64_t m, int64_t nnz) {
-    std::lock_guard<std::mutex> lk(g_hint_mu);
-    for (auto& h : g_hints)
-        if (h.rowptr == rowptr && h.m == m) { h.nnz = nnz; return; }
-    g_hints[g_hint_next] = NnzHint{rowptr, m, nnz};
-    g_hint_next = (g_hint_next + 1) % 16;
-}
-
-int64_t lookup_nnz(const void* rowptr, int64_t m) {
-    std::lock_guard<std::mutex> lk(g_hint_mu);
-    for (const auto& h : g_hints)
-        if (h.rowptr == rowptr && h.m == m) return h.nnz;
-    return -1;
 }
 
 template <int V, int G, int NV>
@@ -261,7 +273,7 @@ int da_spmm(int64_t m, int64_t k, int64_t N, const int32_t* rowptr, const int32_
     const bool cm = (algo & 2) != 0;
     const bool pr = (algo & 1) != 0;
     Geometry g;
-    const int st = pick_geometry(cm, pr, eb, N, B, C, &g);
+    const int st = pick_geometry(cm, pr, eb, N, B, C, eb ? lookup_nnz(rowptr, m) : -1, &g);
     if (st != DA_OK) return st;
     const Family fam = eb ? (pr ? EB_PR : EB_SR) : (pr ? RB_PR : RB_SR);
     return dispatch(fam, g, p);

@@ -133,6 +133,32 @@ __device__ __forceinline__ int row_of_entry(const int* __restrict__ rowptr, int 
     return lo;
 }
 
+// The same search done by the G lanes of a group together: every step probes G rows at once and
+// narrows [lo, hi] to 1/(G+1) of its width, so it takes log_{G+1}(m) dependent loads instead of
+// log_2(m).  All lanes of the group must call it together with the same q; j = lane index inside
+// the group, shift = index of the group's first lane in the wave.
+template <int G>
+__device__ __forceinline__ int row_of_entry_group(const int* __restrict__ rowptr, int lo, int hi, int q,
+                                                  int j, int shift) {
+    if constexpr (G < 4) {
+        return row_of_entry(rowptr, lo, hi, q);
+    } else {
+        while (lo < hi) {
+            const long len = hi - lo;
+            const int r = lo + (int)((len * (j + 1)) / (G + 1));       // lo <= r < hi
+            const bool above = rowptr[r + 1] > q;                      // owner row is <= r
+            unsigned long long bits = __ballot(above) >> shift;
+            if constexpr (G < 64) bits &= (1ull << G) - 1;
+            const int nfalse = G - __popcll(bits);                     // probes 0..nfalse-1 are too low
+            const int new_lo = nfalse == 0 ? lo : lo + (int)((len * nfalse) / (G + 1)) + 1;
+            const int new_hi = nfalse == G ? hi : lo + (int)((len * (nfalse + 1)) / (G + 1));
+            lo = new_lo;
+            hi = new_hi;
+        }
+        return lo;
+    }
+}
+
 // entries a lane group stages per batch
 template <int G> struct StageBatch { static constexpr int value = G < kU ? kU : G; };
 
@@ -404,7 +430,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     for (long c0l = worker * chunk; c0l < nnz; c0l += nworkers * chunk) {
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);
-        int row = row_of_entry(rowptr, 0, m - 1, c0);
+        int row = row_of_entry_group<G>(rowptr, 0, m - 1, c0, j, g * G);
         int row_end = rowptr[row + 1];
         bool shared_with_prev = rowptr[row] < c0;          // only the chunk's first row can be
         Acc<V, NV> acc;
@@ -491,8 +517,8 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     for (long c0l = wave_id * chunk; c0l < nnz; c0l += nwaves * chunk) {
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);
-        const int row_lo = row_of_entry(rowptr, 0, m - 1, c0);
-        const int row_hi = row_of_entry(rowptr, row_lo, m - 1, c1 - 1);
+        const int row_lo = row_of_entry_group<kWave>(rowptr, 0, m - 1, c0, lane, 0);
+        const int row_hi = row_of_entry_group<kWave>(rowptr, row_lo, m - 1, c1 - 1, lane, 0);
         Acc<V, NV> carry;
         carry.clear();
         int carry_row = -1;

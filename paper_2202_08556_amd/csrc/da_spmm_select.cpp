@@ -9,7 +9,7 @@ namespace {
 
 struct SelNode {
     int feature;      // index into the feature vector, < 0 for a leaf
-    float threshold;  // go left when x[feature] <= threshold
+    double threshold; // go left when x[feature] <= threshold
     int left;         // child index, or row of kLeafScores for a leaf
     int right;
 };
@@ -45,7 +45,7 @@ extern "C" int da_spmm_select(const da_features* f)
     for (int t = 0; t < kNumTrees; ++t) {
         int i = kTreeRoot[t];
         while (kNodes[i].feature >= 0)
-            i = (x[kNodes[i].feature] <= (double)kNodes[i].threshold) ? kNodes[i].left : kNodes[i].right;
+            i = (x[kNodes[i].feature] <= kNodes[i].threshold) ? kNodes[i].left : kNodes[i].right;
         const float* leaf = kLeafScores[kNodes[i].left];
         for (int a = 0; a < DA_NUM_ALGOS; ++a) score[a] += (double)leaf[a];
     }

@@ -335,3 +335,14 @@ def integer_twin(a: CSR, seed: int | None = None) -> CSR:
     mag = rng.integers(1, 4, size=a.colind.size).astype(np.float32)
     sign = rng.integers(0, 2, size=a.colind.size).astype(np.float32) * 2.0 - 1.0
     return CSR(a.m, a.k, a.rowptr, a.colind, mag * sign, a.name + "_int", a.seed)
+
+
+if __name__ == "__main__":
+    # python -m paper_2202_08556_amd.generators <uniform|powerlaw|stencil|skewed> <out.bin>
+    # writes the column indices of the benchmark configuration as raw int32 (input of `ceilings file`)
+    import sys
+    maker = dict(uniform=lambda: uniform_csr(seed=config_seed(1)), powerlaw=lambda: powerlaw_csr(seed=config_seed(2)),
+                 stencil=lambda: stencil27_csr(seed=config_seed(3)), skewed=lambda: skewed_csr(seed=config_seed(4)))
+    a_ = maker[sys.argv[1]]()
+    a_.colind.tofile(sys.argv[2])
+    print(f"{sys.argv[1]}: m={a_.m} k={a_.k} nnz={a_.nnz} -> {sys.argv[2]}")

@@ -1,0 +1,183 @@
+"""Train the data-aware selector (paper Sec. 5) from sweep timings and compile it into the library.
+
+    python -m paper_2202_08556_amd.selector_train \
+        --train paper_2202_08556_amd/selector_data/train.jsonl paper_2202_08556_amd/selector_data/families.jsonl \
+        --eval paper_2202_08556_amd/selector_data/eval.jsonl
+
+The paper trains a gradient-boosted tree classifier (LightGBM) on `nnz, mat_size, std_row, N`
+(Table 2).  LightGBM is not available here, so the model is a small gradient-boosted forest built
+from scikit-learn regression trees: every tree predicts, for all 8 algorithms at once, the log of
+the slow-down against the best algorithm on that input (squared loss, shrinkage), and the selector
+picks the algorithm with the smallest predicted slow-down.  Training on slow-downs instead of
+arg-min labels makes near-ties harmless.  The model is written as JSON (selector_model.json) and
+as C tables (csrc/selector_model.inc) that da_spmm_select walks.
+
+Figure of merit (Fig. 1 caption, Sec. 5.1): geometric mean over inputs of time(best)/time(chosen).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+
+import numpy as np
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+MODEL_JSON = os.path.join(PKG, "selector_model.json")
+MODEL_INC = os.path.join(PKG, "csrc", "selector_model.inc")
+ALGOS = ["RB+RM+SR", "RB+RM+PR", "RB+CM+SR", "RB+CM+PR", "EB+RM+SR", "EB+RM+PR", "EB+CM+SR", "EB+CM+PR"]
+NUM_FEATURES = 7
+
+
+def feature_vector(f: dict) -> np.ndarray:
+    """Must match the vector built in csrc/da_spmm_select.cpp."""
+    lg = lambda x: np.log2(max(float(x), 1.0))
+    mean = float(f["row_nnz_mean"])
+    mx = float(f["row_nnz_max"])
+    return np.array([
+        lg(f["rows"]), lg(f["nnz"]), np.log2(mean + 1.0),
+        (float(f["row_nnz_std"]) / mean) if mean > 0 else 0.0,
+        np.log2(mx + 1.0), lg(f["N"]),
+        np.log2(mx / mean + 1.0) if mean > 0 else 0.0,
+    ])
+
+
+def load(paths):
+    X, T, meta = [], [], []
+    for p in paths:
+        for line in open(p):
+            r = json.loads(line)
+            X.append(feature_vector(r["features"]))
+            T.append(r["times_us"])
+            meta.append((r["set"], r["name"], r["N"]))
+    return np.array(X), np.array(T, dtype=np.float64), meta
+
+
+def normalized_performance(T, chosen):
+    best = T.min(axis=1)
+    return float(np.exp(np.mean(np.log(best / T[np.arange(len(T)), chosen]))))
+
+
+# ------------------------------------------------------------------------------------------
+# model = list of trees; tree = dict(feature[], threshold[], left[], right[], value[][8])
+# ------------------------------------------------------------------------------------------
+def walk(model, x):
+    score = np.zeros(8)
+    for t in model["trees"]:
+        i = 0
+        while t["feature"][i] >= 0:
+            i = t["left"][i] if x[t["feature"][i]] <= t["threshold"][i] else t["right"][i]
+        score += np.array(t["value"][i])
+    return int(np.argmax(score))           # ties -> lowest id, as in the C code
+
+
+def predict(model, X):
+    return np.array([walk(model, x) for x in X])
+
+
+def fit(X, T, Xval=None, Tval=None, n_trees=60, depth=5, lr=0.15, min_leaf=4, seed=0):
+    from sklearn.tree import DecisionTreeRegressor
+    Y = np.log(T / T.min(axis=1, keepdims=True))          # log slow-down, >= 0
+    Y = np.minimum(Y, np.log(50.0))                        # a 50x loss is as bad as it needs to be
+    base = Y.mean(axis=0)
+    trees = [dict(feature=[-1], threshold=[0.0], left=[0], right=[0], value=[(-base).tolist()])]
+    F = np.tile(base, (len(X), 1))
+    best_model, best_score = None, -1.0
+    rng = np.random.RandomState(seed)
+    for it in range(n_trees):
+        reg = DecisionTreeRegressor(max_depth=depth, min_samples_leaf=min_leaf, random_state=rng.randint(1 << 30))
+        reg.fit(X, Y - F)
+        tr = reg.tree_
+        F += lr * reg.predict(X)
+        trees.append(dict(feature=[int(f) if f >= 0 else -1 for f in tr.feature],
+                          threshold=[float(t) for t in tr.threshold],
+                          left=[int(c) for c in tr.children_left], right=[int(c) for c in tr.children_right],
+                          value=[(-lr * tr.value[i, :, 0]).tolist() for i in range(tr.node_count)]))
+        if Xval is not None:
+            model = dict(trees=list(trees))
+            sc = normalized_performance(Tval, predict(model, Xval))
+            if sc > best_score + 1e-6:
+                best_score, best_model = sc, model
+    if Xval is None:
+        return dict(trees=trees)
+    return best_model
+
+
+def write_inc(model, path, note):
+    nodes, leaves, roots = [], [], []
+    for t in model["trees"]:
+        off = len(nodes)
+        roots.append(off)
+        for i in range(len(t["feature"])):
+            if t["feature"][i] < 0:
+                nodes.append((-1, 0.0, len(leaves), 0))
+                leaves.append(t["value"][i])
+            else:
+                nodes.append((t["feature"][i], t["threshold"][i], off + t["left"][i], off + t["right"][i]))
+    with open(path, "w") as f:
+        f.write("// Selector model: a gradient-boosted forest of regression trees over the feature vector built in\n"
+                "// da_spmm_select.cpp; a leaf holds minus the predicted log slow-down of each algorithm and the\n"
+                "// selector takes the arg-max of the summed leaves.  Written by selector_train.py -- do not edit.\n")
+        f.write(f"// {note}\n")
+        f.write("// Node layout: feature < 0 marks a leaf whose `left` field indexes kLeafScores.\n")
+        f.write(f"static const int kNumTrees = {len(roots)};\n")
+        f.write(f"static const int kTreeRoot[{len(roots)}] = {{" + ", ".join(map(str, roots)) + "};\n")
+        f.write(f"static const SelNode kNodes[{len(nodes)}] = {{\n")
+        for n in nodes:
+            f.write(f"    {{{n[0]}, {n[1]!r}, {n[2]}, {n[3]}}},\n")
+        f.write("};\n")
+        f.write(f"static const float kLeafScores[{len(leaves)}][8] = {{\n")
+        for v in leaves:
+            f.write("    {" + ", ".join(f"{x:.6g}f" for x in v) + "},\n")
+        f.write("};\n")
+
+
+def report(name, T, chosen, lines):
+    lines.append(f"{name}: {len(T)} inputs; selector normalised performance {normalized_performance(T, chosen):.4f}")
+    for a in range(8):
+        lines.append(f"    static {ALGOS[a]}: {normalized_performance(T, np.full(len(T), a)):.4f}"
+                     f"   (best on {int(np.sum(T.argmin(axis=1) == a))} inputs, chosen on {int(np.sum(chosen == a))})")
+    loss = T[np.arange(len(T)), chosen] / T.min(axis=1)
+    lines.append(f"    worst slow-down of the selector {loss.max():.2f}x; inputs with > 1.25x: {int(np.sum(loss > 1.25))}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--train", nargs="+", required=True)
+    ap.add_argument("--eval", nargs="+", required=True)
+    ap.add_argument("--trees", type=int, default=60)
+    ap.add_argument("--depth", type=int, default=5)
+    ap.add_argument("--report", default=os.path.join(PKG, "selector_data", "report.txt"))
+    ap.add_argument("--no-write", action="store_true")
+    args = ap.parse_args()
+    Xtr, Ttr, _ = load(args.train)
+    Xev, Tev, _ = load(args.eval)
+    lines = []
+    # (a) the paper's protocol on the pooled data: 40 % train, 10 % validation, 50 % test
+    Xall, Tall = np.vstack([Xtr, Xev]), np.vstack([Ttr, Tev])
+    perm = np.random.RandomState(1).permutation(len(Xall))
+    n4, n5 = int(0.4 * len(perm)), int(0.5 * len(perm))
+    itr, iva, ite = perm[:n4], perm[n4:n5], perm[n5:]
+    m = fit(Xall[itr], Tall[itr], Xall[iva], Tall[iva], n_trees=args.trees, depth=args.depth)
+    report("pooled 40/10/50 split, test half (Sec. 5.2 protocol)", Tall[ite], predict(m, Xall[ite]), lines)
+    # (b) shipped model: trained on the training sets only (10 % of them held out to pick the
+    #     number of trees), scored on the never-seen evaluation sweep
+    perm = np.random.RandomState(2).permutation(len(Xtr))
+    nv = max(1, len(perm) // 10)
+    model = fit(Xtr[perm[nv:]], Ttr[perm[nv:]], Xtr[perm[:nv]], Ttr[perm[:nv]], n_trees=args.trees, depth=args.depth)
+    report("evaluation sweep (64 matrices x 6 N, disjoint seeds from training)", Tev, predict(model, Xev), lines)
+    report("training sets (resubstitution)", Ttr, predict(model, Xtr), lines)
+    lines.append(f"model: {len(model['trees'])} trees, depth <= {args.depth}; "
+                 f"trained on {len(Xtr)} inputs from {', '.join(os.path.basename(p) for p in args.train)}")
+    text = "\n".join(lines)
+    print(text)
+    if not args.no_write:
+        json.dump(model, open(MODEL_JSON, "w"))
+        write_inc(model, MODEL_INC, f"trained on {len(Xtr)} inputs; evaluation-sweep normalised performance "
+                                    f"{normalized_performance(Tev, predict(model, Xev)):.4f}")
+        os.makedirs(os.path.dirname(args.report), exist_ok=True)
+        open(args.report, "w").write(text + "\n")
+
+
+if __name__ == "__main__":
+    main()
