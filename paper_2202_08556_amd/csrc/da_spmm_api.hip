@@ -136,12 +136,13 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
         if (pr) g.chunk = kEntriesPerWavePR;
         else g.chunk = g.G >= 8 ? 256 : (g.G == 4 ? 128 : 64);
         if (known_nnz >= 0) {
-            // Small matrices: shrink the chunks until there are about two workers per hardware
-            // slot (8 waves on each of 4 SIMDs per CU), so that the chunk walk, which is a chain of
-            // dependent memory round trips, does not set the run time.
-            const long slots = (long)cu_count() * 32 * (pr ? 1 : kWave / g.G);
-            const int floor_ = pr ? 64 : 32;
-            long want = known_nnz / (2 * slots);
+            // Small matrices: shrink the chunks until there are about four waves of workers per
+            // SIMD, so that the chunk walk, a chain of dependent memory round trips, does not set
+            // the run time.  Lane-sized workers (G < 8) keep their chunk: their search cost per
+            // entry is already high.
+            const long workers = (long)cu_count() * 16 * (pr ? 1 : kWave / g.G);
+            const int floor_ = pr ? 64 : (g.G >= 8 ? 32 : g.chunk);
+            long want = known_nnz / workers;
             want = (want + 7) / 8 * 8;
             if (want < floor_) want = floor_;
             if (want < g.chunk) g.chunk = (int)want;

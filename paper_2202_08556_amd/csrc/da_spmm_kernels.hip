@@ -164,6 +164,27 @@ template <int G> struct StageBatch { static constexpr int value = G < kU ? kU : 
 
 template <int U> struct Count { static constexpr int value = U; };
 
+// A lane's share of a staged batch of SB stored entries (lane j of the group holds entries j, j+G,
+// ...).  The next batch is fetched into registers while the current one is being consumed from LDS,
+// so the (colind, val) round trip is off the critical path.
+template <int G, int SB>
+struct BatchRegs {
+    int2 e[SB / G];
+    __device__ __forceinline__ void fetch(const int* __restrict__ colind, const float* __restrict__ vals,
+                                          int p0, int end, int j) {
+#pragma unroll
+        for (int i = 0; i < SB / G; ++i) {
+            const int p = p0 + j + i * G;
+            e[i] = make_int2(0, 0);
+            if (p < end) { e[i].x = colind[p]; e[i].y = __float_as_int(vals[p]); }
+        }
+    }
+    __device__ __forceinline__ void put(int2* st, int j) const {
+#pragma unroll
+        for (int i = 0; i < SB / G; ++i) st[j + i * G] = e[i];
+    }
+};
+
 // Which column tile a block works on and its rank among the blocks of that tile.
 //   pin_tiles == 0: 2-D grid, blockIdx.y = tile.
 //   pin_tiles in {2,4,8}: 1-D grid whose size is a multiple of 8.  Consecutive workgroups go to
@@ -240,15 +261,12 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
         }
     } else {
         int2* st = stage + (wave * RPW + g) * SB;
+        BatchRegs<G, SB> next;
+        next.fetch(colind, vals, start, end, j);
         for (int p0 = start; p0 < end; p0 += SB) {
-#pragma unroll
-            for (int i = j; i < SB; i += G) {
-                const int p = p0 + i;
-                int2 e = make_int2(0, 0);
-                if (p < end) { e.x = colind[p]; e.y = __float_as_int(vals[p]); }
-                st[i] = e;
-            }
+            next.put(st, j);
             wave_lds_sync();
+            if (p0 + SB < end) next.fetch(colind, vals, p0 + SB, end, j);
             if (nvec > 0) {
                 for_blocks<UL>(min(SB, end - p0), [&](auto uc, int t) {
                     constexpr int UU = decltype(uc)::value;
@@ -321,12 +339,12 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
         }
     } else {
         int2* st = stage + wave * kWave;
+        BatchRegs<kWave, kWave> next;
+        next.fetch(colind, vals, start, end, lane);
         for (int p0 = start; p0 < end; p0 += kWave) {
-            const int p = p0 + lane;
-            int2 e = make_int2(0, 0);
-            if (p < end) { e.x = colind[p]; e.y = __float_as_int(vals[p]); }
-            st[lane] = e;
+            next.put(st, lane);
             wave_lds_sync();
+            if (p0 + kWave < end) next.fetch(colind, vals, p0 + kWave, end, lane);
             const int cnt = min(kWave, end - p0);
             if (nvec > 0) {
                 for_blocks<UL>(cnt / S, [&](auto uc, int t) {
@@ -436,16 +454,13 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
         Acc<V, NV> acc;
         acc.clear();
 
+        BatchRegs<G, SB> next;
+        if constexpr (G > 1) next.fetch(colind, vals, c0, c1, j);
         for (int q0 = c0; q0 < c1; q0 += SB) {
             if constexpr (G > 1) {
-#pragma unroll
-                for (int i = j; i < SB; i += G) {
-                    const int q = q0 + i;
-                    int2 e = make_int2(0, 0);
-                    if (q < c1) { e.x = colind[q]; e.y = __float_as_int(vals[q]); }
-                    st[i] = e;
-                }
+                next.put(st, j);
                 wave_lds_sync();
+                if (q0 + SB < c1) next.fetch(colind, vals, q0 + SB, c1, j);
             }
             for_blocks<UL>(min(SB, c1 - q0), [&](auto uc, int t) {
                 constexpr int UU = decltype(uc)::value;

@@ -99,9 +99,10 @@ def run_matrix(a, tag, member, setname, out, done, ns=NS):
         Bs = [torch.empty((a.k, N), device=dev).uniform_(-1.0, 1.0, generator=g) for _ in range(COPIES)]
         Cs = [torch.empty((a.m, N), device=dev) for _ in range(COPIES)]
         times, reps = [], []
+        runs = [da.PreparedSpmm(a.m, a.k, N, rp, ci, va, Bs[i], Cs[i]) for i in range(COPIES)]
         for algo in range(da.DA_NUM_ALGOS):
             def call(i, algo=algo):
-                da.da_spmm(a.m, a.k, N, rp, ci, va, Bs[i % COPIES], Cs[i % COPIES], algo)
+                runs[i % COPIES](algo)
             t, r = time_algo(call)
             times.append(round(t, 2))
             reps.append(r)
@@ -112,7 +113,7 @@ def run_matrix(a, tag, member, setname, out, done, ns=NS):
         best = int(np.argmin(times))
         print(f"{setname} {tag} N={N}: best {da.ALGO_NAMES[best]} {times[best]:.1f} us  " +
               " ".join(f"{t:.0f}" for t in times), flush=True)
-        del Bs, Cs
+        del runs, Bs, Cs
     del rp, ci, va
 
 
