@@ -48,15 +48,19 @@ __device__ __forceinline__ void wave_lds_sync() {
 // every group of G lanes gathers T rows (indices idx[group*T ..]); blockIdx.y = column tile
 template <int V, int G>
 __global__ __launch_bounds__(256) void gather_kernel(const int* __restrict__ idx, const float* __restrict__ B,
-                                                     float* __restrict__ out, int N, int T, long ngroups)
+                                                     float* __restrict__ out, int N, int T, long ngroups, int pin)
 {
     constexpr int U = 8, SB = G < U ? U : G;
     __shared__ int stage[4 * (64 / G) * SB];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane / G, j = lane % G;
-    const long group = ((long)blockIdx.x * 4 + wave) * (64 / G) + g;
+    // pin > 0: 1-D grid, column tile = (blockIdx.x % 8) % pin, i.e. fixed per XCD
+    int tile = blockIdx.y;
+    long bx = blockIdx.x;
+    if (pin > 0) { const int xcd = blockIdx.x & 7; tile = xcd % pin; bx = (long)(blockIdx.x >> 3) * (8 / pin) + xcd / pin; }
+    const long group = (bx * 4 + wave) * (64 / G) + g;
     if (group >= ngroups) return;
     const int* my = idx + group * T;
-    const float* Bn = B + (blockIdx.y * G + j) * V;
+    const float* Bn = B + (tile * G + j) * V;
     float acc[V];
     for (int v = 0; v < V; ++v) acc[v] = 0;
     int* st = stage + (wave * (64 / G) + g) * SB;
@@ -103,11 +107,16 @@ template <int V, int G>
 void run_gather(const int* didx, const float* dB, float* dout, int N, int T, long nidx) {
     if (N % (G * V) != 0 || T % (G < 8 ? 8 : G) != 0) return;
     const long ngroups = nidx / T, gpb = 4 * (64 / G);
-    const dim3 grid((unsigned)((ngroups + gpb - 1) / gpb), N / (G * V));
-    const float ms = timeit([&] { hipLaunchKernelGGL((gather_kernel<V, G>), grid, dim3(256), 0, 0, didx, dB, dout, N, T, ngroups); });
-    std::printf("  %d-byte loads, %2d lanes per row, %d column tile(s), %d rows per lane group: %8.1f us  %6.2f TB/s\n",
-                4 * V, G, N / (G * V), T, ms * 1e3, (double)ngroups * T * N * 4 / ms / 1e9);
-    std::fflush(stdout);
+    const int tiles = N / (G * V);
+    for (int pin = 0; pin <= ((tiles == 2 || tiles == 4 || tiles == 8) ? 1 : 0); ++pin) {
+        const long bx = (ngroups + gpb - 1) / gpb;
+        const dim3 grid = pin ? dim3((unsigned)(8 * ((bx + 8 / tiles - 1) / (8 / tiles))), 1) : dim3((unsigned)bx, tiles);
+        const int pinarg = pin ? tiles : 0;
+        const float ms = timeit([&] { hipLaunchKernelGGL((gather_kernel<V, G>), grid, dim3(256), 0, 0, didx, dB, dout, N, T, ngroups, pinarg); });
+        std::printf("  %d-byte loads, %2d lanes per row, %d column tile(s)%s, %d rows per lane group: %8.1f us  %6.2f TB/s\n",
+                    4 * V, G, tiles, pin ? " pinned to XCDs" : "", T, ms * 1e3, (double)ngroups * T * N * 4 / ms / 1e9);
+        std::fflush(stdout);
+    }
 }
 
 void gather_all(const std::vector<int>& idx, long k, int N) {

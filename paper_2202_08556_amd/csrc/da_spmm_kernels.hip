@@ -123,6 +123,31 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Sum over the lanes of a wave that share lane % G (the slots of a PR kernel); every lane ends up
+// with the total.  Butterfly steps at distance 32 and 16 use the gfx950 lane-swap instructions,
+// the steps inside a 16-lane row use DPP rotations fused into the add: no LDS round trips.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+    return x + __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), CTRL, 0xf, 0xf, false));
+}
+
+template <int G>
+__device__ __forceinline__ float slot_allreduce(float x) {
+    if constexpr (G <= 32) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    if constexpr (G <= 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+        x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    if constexpr (G <= 8) x = dpp_add<0x128>(x);   // row_ror:8
+    if constexpr (G <= 4) x = dpp_add<0x124>(x);   // row_ror:4
+    if constexpr (G <= 2) x = dpp_add<0x122>(x);   // row_ror:2
+    if constexpr (G <= 1) x = dpp_add<0x121>(x);   // row_ror:1
+    return x;
+}
+
 // Smallest r in [lo, hi] with rowptr[r+1] > q: the row that owns stored entry q (rows without
 // entries are skipped).  Requires rowptr[lo] <= q < rowptr[hi+1].
 __device__ __forceinline__ int row_of_entry(const int* __restrict__ rowptr, int lo, int hi, int q) {
@@ -160,7 +185,7 @@ __device__ __forceinline__ int row_of_entry_group(const int* __restrict__ rowptr
 }
 
 // entries a lane group stages per batch
-template <int G> struct StageBatch { static constexpr int value = G < kU ? kU : G; };
+template <int G> struct StageBatch { static constexpr int value = G < 8 ? kU : (G < 32 ? 32 : G); };
 
 template <int U> struct Count { static constexpr int value = U; };
 
@@ -371,12 +396,9 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
     }
     // reduction tree over the slots: lanes with equal j
 #pragma unroll
-    for (int d = kWave / 2; d >= G; d >>= 1) {
+    for (int i = 0; i < NV; ++i)
 #pragma unroll
-        for (int i = 0; i < NV; ++i)
-#pragma unroll
-            for (int v = 0; v < V; ++v) acc.a[i][v] += __shfl_down(acc.a[i][v], d, kWave);
-    }
+        for (int v = 0; v < V; ++v) acc.a[i][v] = slot_allreduce<G>(acc.a[i][v]);
     if (s == 0 && nvec > 0) acc.emit(C + row * N + n0, nvec, false);
 }
 
@@ -475,16 +497,24 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
 #pragma unroll
                     for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * N, nvec);
                 }
+                if (row_end > q0 + t + UU) {
+                    // the common case: the whole block lies inside the current row
+                    if (nvec > 0) {
 #pragma unroll
-                for (int u = 0; u < UU; ++u) {
-                    if (nvec > 0) acc.fma(__int_as_float(e[u].y), b[u]);
-                    const int next = q0 + t + u + 1;
-                    if (next == row_end) {                     // the row is complete
-                        if (nvec > 0) acc.emit(Cn + (long)row * N, nvec, shared_with_prev);
-                        acc.clear();
-                        shared_with_prev = false;
-                        if (next < c1) {
-                            do { ++row; row_end = rowptr[row + 1]; } while (row_end <= next);
+                        for (int u = 0; u < UU; ++u) acc.fma(__int_as_float(e[u].y), b[u]);
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < UU; ++u) {
+                        if (nvec > 0) acc.fma(__int_as_float(e[u].y), b[u]);
+                        const int next = q0 + t + u + 1;
+                        if (next == row_end) {                 // the row is complete
+                            if (nvec > 0) acc.emit(Cn + (long)row * N, nvec, shared_with_prev);
+                            acc.clear();
+                            shared_with_prev = false;
+                            if (next < c1) {
+                                do { ++row; row_end = rowptr[row + 1]; } while (row_end <= next);
+                            }
                         }
                     }
                 }
