@@ -3,8 +3,9 @@
 //   ceilings stream                      HBM read and copy bandwidth, 1 GiB buffers
 //   ceilings gather N k uniform|zipf     random gather of k rows of N floats (13 Mi indices), the
 //                                        access pattern of the B operand, without values/FMA/C
-//   ceilings file colind.bin k N         the same over a real column-index stream (raw int32 file,
-//                                        e.g. written by `python -m paper_2202_08556_amd.generators`)
+//   ceilings file colind.bin k N [T]     the same over a real column-index stream (raw int32 file,
+//                                        e.g. written by `python -m paper_2202_08556_amd.generators`);
+//                                        with T also with every block of T indices sorted ascending
 //   ceilings atomics                     fp32 atomic-add rate on random rows and on 16 hot rows
 // The gather kernels use the staging scheme of the product kernels: a lane group loads a batch
 // of indices coalesced, passes them round through LDS and issues 8 row gathers back to back.
@@ -15,6 +16,7 @@
 #include <cstring>
 #include <random>
 #include <vector>
+#include <algorithm>
 
 #define CK(x) do { hipError_t err_ = (x); if (err_ != hipSuccess) { \
     std::printf("HIP error %s at line %d\n", hipGetErrorString(err_), __LINE__); std::exit(1); } } while (0)
@@ -187,6 +189,21 @@ int main(int argc, char** argv)
             if (idx[i] < 0 || idx[i] >= k) { std::printf("index out of range\n"); return 1; }
         std::printf("gather over %s: %ld indices, k=%ld, N=%d\n", argv[2], n, k, N);
         gather_all(idx, k, N);
+        if (argc >= 6) {
+            // every lane group's T indices in ascending order: all groups then sweep the rows of B
+            // from low to high addresses at about the same pace
+            const long T = std::atol(argv[5]);
+            if (T < 32 || T % 32) { std::printf("T must be a multiple of 32\n"); return 1; }
+            for (long b = 0; b + T <= n; b += T) std::sort(idx.begin() + b, idx.begin() + b + T);
+            std::printf("same stream, every block of %ld indices sorted ascending\n", T);
+            const long nidx = n / T * T;
+            int* didx; float* dB; float* dout;
+            CK(hipMalloc(&dout, 4)); CK(hipMalloc(&didx, nidx * 4)); CK(hipMalloc(&dB, (size_t)k * N * 4));
+            CK(hipMemcpy(didx, idx.data(), nidx * 4, hipMemcpyHostToDevice)); CK(hipMemset(dB, 0, (size_t)k * N * 4));
+            if (N >= 128) { run_gather<4, 32>(didx, dB, dout, N, (int)T, nidx); run_gather<4, 8>(didx, dB, dout, N, (int)T, nidx); }
+            else if (N >= 32) run_gather<4, 8>(didx, dB, dout, N, (int)T, nidx);
+            else run_gather<1, 8>(didx, dB, dout, N, (int)T, nidx);
+        }
     } else if (!std::strcmp(mode, "atomics")) {
         const int n = 1 << 20, N = 64;
         const long rows = 262144;

@@ -529,15 +529,31 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
 // ------------------------------------------------------------------------------------------
 // EB + PR : a wave owns `chunk` consecutive stored entries and takes them 64 at a time.  The
 // lanes form S = 64/G slots (times G lanes along n); in one step slot s holds the product vector
-// of one entry together with that entry's row index.  The slots are combined with the
+// of one entry together with that entry's row index.
+//
+// A step whose entries all belong to one row needs no cross-lane traffic: every slot adds its
+// product to its own partial sum of the current row (as the RB+PR kernel does); the slots are
+// combined only when the row ends.  A step that contains a row boundary is combined with the
 // CONDITIONAL REDUCTION of Sec. 4 (Fig. 6(e)): a log-step network in which slot s adds the value
-// of slot s+d only if both carry the same row index.  Because entries are stored row after row,
-// afterwards the leftmost slot of every run of equal indices holds the sum of the run (the
-// validity rule of Sec. 4).  Runs that end inside the step are written by their leftmost slot;
-// the run that reaches the last slot and whose row is not finished is carried into the next step.
-// Rows that are complete inside the chunk get one plain store; only the first and last row of a
-// chunk, when shared with the neighbouring chunks, are combined with atomic adds.
+// of slot s+d only if both belong to the same row.  Because entries are stored row after row,
+// afterwards the leftmost slot of every run of equal row indices holds the sum of the run (the
+// validity rule of Sec. 4); whether slot s+d is in the same run is decided once, from a ballot of
+// the run heads, instead of comparing shuffled row indices in every step of the network.  The run
+// that starts the step is merged with the partial sums carried so far, runs that end inside the
+// step are written by their leftmost slot, and the run that reaches the end of the step
+// unfinished becomes the new set of per-slot partial sums.  Rows that are complete inside the
+// chunk get one plain store; only the first and last row of a chunk, when shared with the
+// neighbouring chunks, are combined with atomic adds.
 // ------------------------------------------------------------------------------------------
+template <int V, int G, int NV>
+__device__ __forceinline__ Acc<V, NV> slots_allreduce(Acc<V, NV> x) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int v = 0; v < V; ++v) x.a[i][v] = slot_allreduce<G>(x.a[i][v]);
+    return x;
+}
+
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
@@ -564,29 +580,40 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
         const int c1 = (int)min(c0l + chunk, (long)nnz);
         const int row_lo = row_of_entry_group<kWave>(rowptr, 0, m - 1, c0, lane, 0);
         const int row_hi = row_of_entry_group<kWave>(rowptr, row_lo, m - 1, c1 - 1, lane, 0);
-        Acc<V, NV> carry;
-        carry.clear();
-        int carry_row = -1;
-        bool carry_started = false;
+        Acc<V, NV> acc;                                    // per-slot partial sums of row `cur`
+        acc.clear();
+        int cur = -1;                                      // row being accumulated (wave-uniform)
+        bool cur_started = false;                          // its first entry lies in this chunk
+        int scan_row = row_lo;                             // lower bound for the row lookups
 
         for (int q0 = c0; q0 < c1; q0 += kWave) {
             // every lane fetches one entry and finds its row (binary search restricted to the
             // rows of this chunk) and whether it is the first / last entry of that row
             const int q = q0 + lane;
+            const int cnt = min(kWave, c1 - q0);
             int4 mine = make_int4(0, 0, -1, 0);
+            // `scan_row` owns entry q0 or precedes its row; when its entries reach past this batch
+            // no lane has to search
+            const int scan_start = rowptr[scan_row], scan_end = rowptr[scan_row + 1];
+            const bool one_row = scan_start <= q0 && scan_end >= q0 + cnt;
             if (q < c1) {
-                const int r = row_of_entry(rowptr, row_lo, row_hi, q);
+                int r = scan_row, r_start = scan_start, r_end = scan_end;
+                if (!one_row) {
+                    r = row_of_entry(rowptr, scan_row, row_hi, q);
+                    r_start = rowptr[r];
+                    r_end = rowptr[r + 1];
+                }
                 mine.x = colind[q];
                 mine.y = __float_as_int(vals[q]);
                 mine.z = r;
-                mine.w = (q == rowptr[r] ? 1 : 0) | (q + 1 == rowptr[r + 1] ? 2 : 0);
+                mine.w = (q == r_start ? 1 : 0) | (q + 1 == r_end ? 2 : 0);
             }
+            scan_row = __shfl(mine.z, cnt - 1, kWave);            // row of the batch's last entry
             if constexpr (G > 1) { st[lane] = mine; wave_lds_sync(); }
-            const int cnt = min(kWave, c1 - q0);
 
             for (int tb = 0; tb * S < cnt; tb += UU) {
                 int4 e[UU];
-                Acc<V, NV> x[UU];
+                Acc<V, NV> b[UU];
 #pragma unroll
                 for (int u = 0; u < UU; ++u) {
                     if constexpr (G > 1) e[u] = st[((tb + u) * S + s) & (kWave - 1)]; else e[u] = mine;
@@ -595,7 +622,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                 // branch-free gathers: slots past the end of the chunk hold column 0
                 if (nvec > 0) {
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) x[u].load(Bn + (long)e[u].x * N, nvec);
+                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * N, nvec);
                 }
 #pragma unroll
                 for (int u = 0; u < UU; ++u) {
@@ -604,57 +631,85 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                     const int er = e[u].z;
                     const bool evalid = er >= 0;
                     const float a = __int_as_float(e[u].y);
-#pragma unroll
-                    for (int i = 0; i < NV; ++i)
-#pragma unroll
-                        for (int v = 0; v < V; ++v)
-                            x[u].a[i][v] = (evalid && nvec > 0) ? a * x[u].a[i][v] : 0.f;
-                    // conditional reduction network over the slots
-#pragma unroll
-                    for (int d = 1; d < S; d <<= 1) {
-                        const int orow = __shfl_down(er, d * G, kWave);
-                        const bool take = (s + d < S) && (orow == er);
-#pragma unroll
-                        for (int i = 0; i < NV; ++i)
-#pragma unroll
-                            for (int v = 0; v < V; ++v) {
-                                const float ox = __shfl_down(x[u].a[i][v], d * G, kWave);
-                                if (take) x[u].a[i][v] += ox;
-                            }
-                    }
-                    const int prow = __shfl_up(er, G, kWave);
-                    const bool head = evalid && (s == 0 || prow != er);
                     const int nv = min(S, cnt - t0);                   // valid slots in this step
-                    const int tail_lane = (nv - 1) * G;
-                    const int tail_row = __shfl(er, tail_lane, kWave);
-                    const bool tail_ended = (__shfl(e[u].w, tail_lane, kWave) & 2) != 0;
-                    bool started = (e[u].w & 1) != 0;
-                    if (s == 0 && carry_row == er) {                    // continue the carried run
-                        x[u].add(carry);
-                        started = carry_started;
-                    }
-                    const bool in_tail_run = evalid && er == tail_row;
-                    if (head && nvec > 0 && (!in_tail_run || tail_ended))
-                        x[u].emit(Cn + (long)er * N, nvec, !started);
-                    if (!tail_ended) {
-                        // leftmost slot of the tail run -> every slot keeps a copy of the carry
-                        const unsigned long long mask = __ballot(in_tail_run);
-                        const int src = (__ffsll((long long)mask) - 1) / G * G + j;
+                    const int first_row = __builtin_amdgcn_readfirstlane(er);
+                    const int first_flags = __builtin_amdgcn_readfirstlane(e[u].w);
+                    const int last_row = __shfl(er, (nv - 1) * G, kWave);
+                    const int last_flags = __shfl(e[u].w, (nv - 1) * G, kWave);
+
+                    if (first_row == last_row) {
+                        // one row in the whole step: no cross-lane work
+                        if (cur < 0) { cur = first_row; cur_started = (first_flags & 1) != 0; }
+                        if (evalid && nvec > 0) acc.fma(a, b[u]);
+                        if (last_flags & 2) {                           // the row ends here
+                            const Acc<V, NV> total = slots_allreduce<V, G, NV>(acc);
+                            if (s == 0 && nvec > 0) total.emit(Cn + (long)cur * N, nvec, !cur_started);
+                            acc.clear();
+                            cur = -1;
+                        }
+                    } else {
+                        // a row boundary inside the step: conditional reduction
+                        Acc<V, NV> p;                                   // this slot's product
 #pragma unroll
                         for (int i = 0; i < NV; ++i)
 #pragma unroll
-                            for (int v = 0; v < V; ++v) carry.a[i][v] = __shfl(x[u].a[i][v], src, kWave);
-                        carry_started = __shfl((int)started, src, kWave) != 0;
-                        carry_row = tail_row;
-                    } else {
-                        carry_row = -1;
+                            for (int v = 0; v < V; ++v)
+                                p.a[i][v] = (evalid && nvec > 0) ? a * b[u].a[i][v] : 0.f;
+                        Acc<V, NV> x = p;
+                        // run heads: a slot whose left neighbour holds another row; the first
+                        // slot past the valid ones counts as a head so that the last run ends there
+                        const int prow = __shfl_up(er, G, kWave);
+                        const bool head = s <= nv && (s == 0 || prow != er);
+                        const unsigned long long heads = __ballot(head);
+                        // slots from s to the end of its run
+                        int dist = S - 1 - s;
+                        if (s < S - 1) {
+                            const unsigned long long above = heads >> ((s + 1) * G);
+                            if (above) dist = (__ffsll((long long)above) - 1) / G;
+                        }
+#pragma unroll
+                        for (int d = 1; d < S; d <<= 1) {
+                            const bool take = d <= dist;
+#pragma unroll
+                            for (int i = 0; i < NV; ++i)
+#pragma unroll
+                                for (int v = 0; v < V; ++v) {
+                                    const float ox = __shfl_down(x.a[i][v], d * G, kWave);
+                                    if (take) x.a[i][v] += ox;
+                                }
+                        }
+                        // the run that starts the step continues the row accumulated so far
+                        bool started = true;                            // runs that begin inside the step
+                        if (cur >= 0) {
+                            const Acc<V, NV> total = slots_allreduce<V, G, NV>(acc);
+                            if (s == 0) { x.add(total); started = cur_started; }
+                        } else if (s == 0) {
+                            started = (first_flags & 1) != 0;
+                        }
+                        const bool last_ended = (last_flags & 2) != 0;
+                        const bool in_last_run = evalid && er == last_row;
+                        if (head && evalid && nvec > 0 && (!in_last_run || last_ended))
+                            x.emit(Cn + (long)er * N, nvec, !started);
+                        if (last_ended) {
+                            acc.clear();
+                            cur = -1;
+                        } else {                                        // unfinished run -> new partial sums
+#pragma unroll
+                            for (int i = 0; i < NV; ++i)
+#pragma unroll
+                                for (int v = 0; v < V; ++v) acc.a[i][v] = in_last_run ? p.a[i][v] : 0.f;
+                            cur = last_row;
+                            cur_started = true;
+                        }
                     }
                 }
             }
             if constexpr (G > 1) wave_lds_sync();
         }
-        if (carry_row >= 0 && s == 0 && nvec > 0)            // row continues in the next chunk
-            carry.emit(Cn + (long)carry_row * N, nvec, true);
+        if (cur >= 0) {                                       // row continues in the next chunk
+            const Acc<V, NV> total = slots_allreduce<V, G, NV>(acc);
+            if (s == 0 && nvec > 0) total.emit(Cn + (long)cur * N, nvec, true);
+        }
     }
 }
 
