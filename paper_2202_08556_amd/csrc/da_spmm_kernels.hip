@@ -561,7 +561,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     int pin_tiles)
 {
     constexpr int S = kWave / G;
-    constexpr int UU = G < kU ? G : kU;                   // steps whose gathers are issued together
+    constexpr int UU = G < 4 ? G : 4;                     // steps whose gathers are issued together
     __shared__ int4 stage[G > 1 ? kBlock : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s = lane / G, j = lane % G;
@@ -584,32 +584,24 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
         acc.clear();
         int cur = -1;                                      // row being accumulated (wave-uniform)
         bool cur_started = false;                          // its first entry lies in this chunk
-        int scan_row = row_lo;                             // lower bound for the row lookups
 
-        for (int q0 = c0; q0 < c1; q0 += kWave) {
-            // every lane fetches one entry and finds its row (binary search restricted to the
-            // rows of this chunk) and whether it is the first / last entry of that row
-            const int q = q0 + lane;
-            const int cnt = min(kWave, c1 - q0);
-            int4 mine = make_int4(0, 0, -1, 0);
-            // `scan_row` owns entry q0 or precedes its row; when its entries reach past this batch
-            // no lane has to search
-            const int scan_start = rowptr[scan_row], scan_end = rowptr[scan_row + 1];
-            const bool one_row = scan_start <= q0 && scan_end >= q0 + cnt;
+        // every lane fetches one entry of a batch and finds its row (binary search restricted to
+        // the rows of this chunk) and whether it is the first / last entry of that row
+        auto lookup = [&](int q) {
+            int4 e = make_int4(0, 0, -1, 0);
             if (q < c1) {
-                int r = scan_row, r_start = scan_start, r_end = scan_end;
-                if (!one_row) {
-                    r = row_of_entry(rowptr, scan_row, row_hi, q);
-                    r_start = rowptr[r];
-                    r_end = rowptr[r + 1];
-                }
-                mine.x = colind[q];
-                mine.y = __float_as_int(vals[q]);
-                mine.z = r;
-                mine.w = (q == r_start ? 1 : 0) | (q + 1 == r_end ? 2 : 0);
+                const int r = row_of_entry(rowptr, row_lo, row_hi, q);
+                e.x = colind[q];
+                e.y = __float_as_int(vals[q]);
+                e.z = r;
+                e.w = (q == rowptr[r] ? 1 : 0) | (q + 1 == rowptr[r + 1] ? 2 : 0);
             }
-            scan_row = __shfl(mine.z, cnt - 1, kWave);            // row of the batch's last entry
+            return e;
+        };
+        for (int q0 = c0; q0 < c1; q0 += kWave) {
+            const int4 mine = lookup(q0 + lane);
             if constexpr (G > 1) { st[lane] = mine; wave_lds_sync(); }
+            const int cnt = min(kWave, c1 - q0);
 
             for (int tb = 0; tb * S < cnt; tb += UU) {
                 int4 e[UU];
