@@ -27,6 +27,8 @@ def problems():
     yield "const_rows", gen.lognormal_csr(3000, 64.0, 0.0, seed=5101), [4, 48]
     yield "one_long_row", gen.skewed_csr(m=64, k=40000, heavy_frac=0.02, heavy_lo=30000,
                                          heavy_hi=30000, light_mean=0.5, seed=9), [8, 12]
+    # wide B: several column tiles with a ragged last one (520 = 2*256 + 8; 1030 is not a multiple of 4)
+    yield "wide_N", gen.skewed_csr(m=900, k=700, heavy_frac=0.01, heavy_lo=300, heavy_hi=600, seed=10), [520, 1030]
 
 
 CASES = [(name, a, N) for name, a, Ns in problems() for N in Ns]
@@ -135,3 +137,67 @@ def test_features_match_oracle(gpu):
         assert got["row_nnz_mean"] == pytest.approx(want["row_nnz_mean"], rel=1e-14)
         assert got["row_nnz_std"] == pytest.approx(want["row_nnz_std"], rel=1e-9, abs=1e-12)
         assert 0 <= da.da_spmm_select(got) < 8
+
+
+def test_side_stream_and_prepared_call(gpu):
+    """The stream argument is honoured and the pre-marshalled call gives the same result."""
+    from paper_2202_08556_amd import binding as da
+    a = gen.lognormal_csr(4000, 12.0, 2.0, seed=77)
+    N = 40
+    B = gen.dense(a.k, N, "uniform", seed=78)
+    c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
+    prob = gpu(a, B)
+    side = torch.cuda.Stream()
+    for algo in ALGOS:
+        C = torch.full((a.m, N), float("nan"), device=prob.B.device)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            run = da.PreparedSpmm(a.m, a.k, N, prob.rowptr, prob.colind, prob.vals, prob.B, C)
+            run(algo)
+        side.synchronize()
+        assert orc.tolerance_ratio(C.cpu().numpy(), c_ref, s_abs) <= 1.0
+        C.fill_(float("nan"))
+        torch.cuda.synchronize()
+        da.da_spmm(a.m, a.k, N, prob.rowptr, prob.colind, prob.vals, prob.B, C, algo, stream=side)
+        side.synchronize()
+        assert orc.tolerance_ratio(C.cpu().numpy(), c_ref, s_abs) <= 1.0
+
+
+def test_tuning_overrides_are_validated_and_correct(gpu, monkeypatch):
+    """Geometry overrides used for measurement runs: valid ones give the same C, invalid ones an error."""
+    import os
+    import subprocess
+    import sys
+    code = r"""
+import os, sys, numpy as np, torch
+sys.path.insert(0, os.getcwd())
+from oracle import reference as orc
+from paper_2202_08556_amd import binding as da, generators as gen
+a = gen.lognormal_csr(3000, 20.0, 3.0, seed=5); N = 128
+B = gen.dense(a.k, N, "uniform", seed=6)
+c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
+dev = torch.device("cuda:0")
+rp, ci, va, Bd = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals, B))
+for env, algos, ok in [(dict(G="8", PIN="1"), (0, 1, 4, 5), True), (dict(G="16", PIN="1", CHUNK="64"), (0, 4), True),
+                       (dict(V="1", G="64"), (0, 4), True), (dict(NV="2"), (2, 3, 6, 7), True),
+                       (dict(G="3"), (0,), False), (dict(V="2"), (0,), False), (dict(G="32"), (1,), False)]:
+    for k in ("V", "G", "NV", "CHUNK", "PIN"):
+        os.environ.pop("DA_SPMM_" + k, None)
+    for k, v in env.items():
+        os.environ["DA_SPMM_" + k] = v
+    for algo in algos:
+        C = torch.full((a.m, N), float("nan"), device=dev)
+        st = da.da_spmm_status(a.m, a.k, N, rp, ci, va, Bd, C, algo)
+        torch.cuda.synchronize()
+        if ok:
+            assert st == 0, (env, algo, st, da.da_spmm_last_error())
+            r = orc.tolerance_ratio(C.cpu().numpy(), c_ref, s_abs)
+            assert r <= 1.0, (env, algo, r)
+        else:
+            assert st == da.DA_ERR_UNSUPPORTED, (env, algo, st)
+print("overrides ok")
+"""
+    env = dict(os.environ, DA_SPMM_TUNE="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=240)
+    assert res.returncode == 0 and "overrides ok" in res.stdout, res.stdout + res.stderr
