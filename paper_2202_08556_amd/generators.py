@@ -27,7 +27,7 @@ import numpy as np
 
 __all__ = [
     "CSR", "uniform_csr", "powerlaw_csr", "stencil27_csr", "skewed_csr", "sweep_csr",
-    "sweep_params", "fig6a_csr", "lognormal_csr", "csr_from_lens", "dense", "dense_int",
+    "sweep_params", "fig6a_csr", "lognormal_csr", "rmat_csr", "csr_from_lens", "dense", "dense_int",
     "integer_twin", "config_seed",
 ]
 
@@ -288,6 +288,46 @@ def sweep_params(j: int, seed_base: int = 5000, max_nnz: int = 2 ** 26):
 def sweep_csr(j: int, seed_base: int = 5000, max_nnz: int = 2 ** 26) -> CSR:
     m, mean_len, cv, seed = sweep_params(j, seed_base, max_nnz)
     return lognormal_csr(m, mean_len, cv, seed, name=f"sweep{j}")
+
+
+# ----------------------------------------------------------------------------------------------
+# R-MAT graphs for the controlled experiments
+# ----------------------------------------------------------------------------------------------
+def rmat_csr(scale: int, edge_factor: float = 16.0, a: float = 0.57, b: float = 0.19, c: float = 0.19,
+             seed: int = 8000, name: str = "rmat") -> CSR:
+    """R-MAT graph on 2^scale nodes (the paper's controlled experiments, Sec. 6.3, synthesise their
+    matrices this way; the parameters are not printed there).  Every edge picks one quadrant of the
+    adjacency matrix per bit with probabilities (a, b, c, d = 1-a-b-c); duplicate edges are dropped
+    and further edges drawn until round(edge_factor * 2^scale) distinct ones exist, so matrices
+    that differ only in (a, b, c) have identical size and sparsity.  Values U(-1,1), columns sorted."""
+    rng = _rng(seed)
+    n = 1 << scale
+    target = int(round(edge_factor * n))
+    if target > n * n:
+        raise ValueError("more edges than matrix entries")
+    keys = np.empty(0, dtype=np.int64)
+    need = target
+    while need > 0:
+        e = int(need * 1.15) + 64
+        rows = np.zeros(e, dtype=np.int64)
+        cols = np.zeros(e, dtype=np.int64)
+        for _ in range(scale):
+            u = rng.random(e)
+            rbit = u >= a + b                       # quadrants c, d: lower half
+            cbit = ((u >= a) & (u < a + b)) | (u >= a + b + c)   # quadrants b, d: right half
+            rows = rows * 2 + rbit
+            cols = cols * 2 + cbit
+        new = np.unique(rows * n + cols)
+        new = new[~np.isin(new, keys, assume_unique=True)] if keys.size else new
+        if new.size > need:
+            new = rng.choice(new, size=need, replace=False)
+        keys = np.concatenate([keys, new])
+        need = target - keys.size
+    keys.sort()
+    lens = np.bincount(keys // n, minlength=n)
+    rowptr = _rowptr_from_lens(lens)
+    colind = (keys % n).astype(np.int32)
+    return CSR(n, n, rowptr, colind, _uniform_vals(rng, colind.size), name, seed)
 
 
 # ----------------------------------------------------------------------------------------------

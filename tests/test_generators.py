@@ -108,3 +108,15 @@ def test_integer_twin_and_dense():
     assert U.dtype == np.float32 and U.min() >= -1 and U.max() < 1 and abs(U.mean()) < 0.05
     G = gen.dense(1000, 8, "normal", seed=1)
     assert 0.9 < G.std() < 1.1
+
+
+def test_rmat_same_size_and_sparsity_different_dispersion():
+    stds = []
+    for i, (a, b, c) in enumerate(((0.25, 0.25, 0.25), (0.45, 0.22, 0.22), (0.57, 0.19, 0.19))):
+        g = gen.rmat_csr(12, 8.0, a, b, c, seed=8100 + i)
+        check_structure(g)
+        assert g.m == g.k == 4096 and g.nnz == 8 * 4096          # identical size and sparsity
+        stds.append(g.row_lengths().std())
+    assert stds[0] < stds[1] < stds[2]                           # skewed quadrants -> dispersed rows
+    again = gen.rmat_csr(12, 8.0, 0.57, 0.19, 0.19, seed=8102)
+    assert np.array_equal(again.colind, g.colind)                 # seeded

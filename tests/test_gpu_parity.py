@@ -27,6 +27,7 @@ def problems():
     yield "const_rows", gen.lognormal_csr(3000, 64.0, 0.0, seed=5101), [4, 48]
     yield "one_long_row", gen.skewed_csr(m=64, k=40000, heavy_frac=0.02, heavy_lo=30000,
                                          heavy_hi=30000, light_mean=0.5, seed=9), [8, 12]
+    yield "rmat", gen.rmat_csr(12, 16.0, 0.57, 0.19, 0.19, seed=8102), [4, 32]
     # wide B: several column tiles with a ragged last one (520 = 2*256 + 8; 1030 is not a multiple of 4)
     yield "wide_N", gen.skewed_csr(m=900, k=700, heavy_frac=0.01, heavy_lo=300, heavy_hi=600, seed=10), [520, 1030]
 
