@@ -167,6 +167,17 @@ def main():
     model = fit(Xtr[perm[nv:]], Ttr[perm[nv:]], Xtr[perm[:nv]], Ttr[perm[:nv]], n_trees=args.trees, depth=args.depth)
     report("evaluation sweep (64 matrices x 6 N, disjoint seeds from training)", Tev, predict(model, Xev), lines)
     report("training sets (resubstitution)", Ttr, predict(model, Xtr), lines)
+    # (c) feature ablation with the paper's protocol: its own four features (Table 2) against the
+    #     extended set compiled into the library.  Columns of the feature vector: 0 log2 rows,
+    #     1 log2 nnz, 2 log2(mean+1), 3 std/mean, 4 log2(max+1), 5 log2 N, 6 log2(max/mean+1).
+    std_abs = Xall[:, 3] * (2.0 ** Xall[:, 2] - 1.0)                 # std of the row length itself
+    paper4 = np.column_stack([Xall[:, 1], Xall[:, 0], np.log2(std_abs + 1.0), Xall[:, 5]])
+    for label, Xf in (("paper's 4 features (nnz, mat_size, std_row, N)", paper4),
+                      ("without the dispersion features (rows, nnz, mean, N)", Xall[:, [0, 1, 2, 5]]),
+                      ("all 7 features", Xall)):
+        mm = fit(Xf[itr], Tall[itr], Xf[iva], Tall[iva], n_trees=args.trees, depth=args.depth)
+        lines.append(f"ablation, pooled 40/10/50 test half, {label}: "
+                     f"{normalized_performance(Tall[ite], predict(mm, Xf[ite])):.4f}")
     lines.append(f"model: {len(model['trees'])} trees, depth <= {args.depth}; "
                  f"trained on {len(Xtr)} inputs from {', '.join(os.path.basename(p) for p in args.train)}")
     text = "\n".join(lines)
