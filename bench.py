@@ -179,6 +179,32 @@ def main():
                      "algorithmic_bytes_per_launch": cbytes},
         "features_ms_once_per_matrix": round(feat_ms, 3), "select_us_per_call": round(select_us, 3),
     }
+    # the same calls captured once in a HIP graph and replayed (no host launch cost per call):
+    # what a launch-latency-bound caller can get; reported beside the eager figure, never as `value`
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        ncap = 30
+        with torch.cuda.stream(side):
+            graph_runs = [da.PreparedSpmm(a.m, a.k, N, c["rp"], c["ci"], c["va"], c["B"], c["C"]) for c in copies]
+            graph_runs[0](chosen)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for i in range(ncap):
+                graph_runs[i % len(graph_runs)](chosen)
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        out["graph_replay_us_per_call"] = round(e0.elapsed_time(e1) / (5 * ncap) * 1e3, 3)
+    except Exception as exc:                               # graph capture is optional information
+        out["graph_replay_us_per_call"] = None
+        log(f"graph capture skipped: {exc}")
     if variants:
         best = min(variants.values())
         out["variants_ms"] = variants

@@ -202,3 +202,37 @@ print("overrides ok")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     res = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=240)
     assert res.returncode == 0 and "overrides ok" in res.stdout, res.stdout + res.stderr
+
+
+def test_calls_can_be_captured_in_a_hip_graph(gpu):
+    """da_spmm only enqueues kernels (no allocation, no synchronisation, no memset nodes), so a
+    sequence of calls can be captured once and replayed; every replay must reproduce the eager
+    result, with eager work and synchronisations between the replays."""
+    from paper_2202_08556_amd import binding as da
+    a = gen.uniform_csr(seed=1000)
+    N = 8
+    B = gen.dense(a.k, N, "uniform", seed=1000)
+    c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
+    prob = gpu(a, B)
+    da.da_spmm_features(a.m, N, prob.rowptr)
+    dev = prob.B.device
+    outs = [torch.full((a.m, N), float("nan"), device=dev) for _ in range(8)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for algo in ALGOS:                                   # warm-up outside capture
+            da.da_spmm(a.m, a.k, N, prob.rowptr, prob.colind, prob.vals, prob.B, outs[algo], algo)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for algo in ALGOS:
+            da.da_spmm(a.m, a.k, N, prob.rowptr, prob.colind, prob.vals, prob.B, outs[algo], algo)
+    for replay in range(3):
+        for o in outs:
+            o.fill_(float("nan"))                            # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for algo in ALGOS:
+            r = orc.tolerance_ratio(outs[algo].cpu().numpy(), c_ref, s_abs)
+            assert r <= 1.0, f"replay {replay} algo {algo}: {r}"
