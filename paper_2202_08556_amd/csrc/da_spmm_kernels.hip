@@ -95,6 +95,12 @@ struct Acc {
 #pragma unroll
             for (int v = 0; v < V; ++v) a[i][v] = fmaf(s, b.a[i][v], a[i][v]);
     }
+    __device__ __forceinline__ void scale(float s) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+#pragma unroll
+            for (int v = 0; v < V; ++v) a[i][v] *= s;
+    }
     __device__ __forceinline__ void add(const Acc& b) {
 #pragma unroll
         for (int i = 0; i < NV; ++i)
@@ -504,9 +510,17 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
                         for (int u = 0; u < UU; ++u) acc.fma(__int_as_float(e[u].y), b[u]);
                     }
                 } else {
+                    // All products first, so that every gather has been waited for before the
+                    // first store or atomic is issued: stores share the in-order memory counter
+                    // with loads, and a store issued between a gather and its use would make the
+                    // wave wait for the store's acknowledgement.
+                    if (nvec > 0) {
+#pragma unroll
+                        for (int u = 0; u < UU; ++u) b[u].scale(__int_as_float(e[u].y));
+                    }
 #pragma unroll
                     for (int u = 0; u < UU; ++u) {
-                        if (nvec > 0) acc.fma(__int_as_float(e[u].y), b[u]);
+                        if (nvec > 0) acc.add(b[u]);
                         const int next = q0 + t + u + 1;
                         if (next == row_end) {                 // the row is complete
                             if (nvec > 0) acc.emit(Cn + (long)row * N, nvec, shared_with_prev);
@@ -616,13 +630,23 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
 #pragma unroll
                     for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * N, nvec);
                 }
+                // all products first: no store or atomic is issued while a gather is outstanding
+                // (stores share the in-order memory counter with loads)
+#pragma unroll
+                for (int u = 0; u < UU; ++u) {
+                    const bool ok = e[u].z >= 0 && nvec > 0;
+                    const float a = __int_as_float(e[u].y);
+#pragma unroll
+                    for (int i = 0; i < NV; ++i)
+#pragma unroll
+                        for (int v = 0; v < V; ++v) b[u].a[i][v] = ok ? a * b[u].a[i][v] : 0.f;
+                }
 #pragma unroll
                 for (int u = 0; u < UU; ++u) {
                     const int t0 = (tb + u) * S;                       // first entry of this step
                     if (t0 >= cnt) break;                              // wave-uniform
                     const int er = e[u].z;
                     const bool evalid = er >= 0;
-                    const float a = __int_as_float(e[u].y);
                     const int nv = min(S, cnt - t0);                   // valid slots in this step
                     const int first_row = __builtin_amdgcn_readfirstlane(er);
                     const int first_flags = __builtin_amdgcn_readfirstlane(e[u].w);
@@ -632,7 +656,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                     if (first_row == last_row) {
                         // one row in the whole step: no cross-lane work
                         if (cur < 0) { cur = first_row; cur_started = (first_flags & 1) != 0; }
-                        if (evalid && nvec > 0) acc.fma(a, b[u]);
+                        acc.add(b[u]);
                         if (last_flags & 2) {                           // the row ends here
                             const Acc<V, NV> total = slots_allreduce<V, G, NV>(acc);
                             if (s == 0 && nvec > 0) total.emit(Cn + (long)cur * N, nvec, !cur_started);
@@ -641,12 +665,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                         }
                     } else {
                         // a row boundary inside the step: conditional reduction
-                        Acc<V, NV> p;                                   // this slot's product
-#pragma unroll
-                        for (int i = 0; i < NV; ++i)
-#pragma unroll
-                            for (int v = 0; v < V; ++v)
-                                p.a[i][v] = (evalid && nvec > 0) ? a * b[u].a[i][v] : 0.f;
+                        const Acc<V, NV> p = b[u];                      // this slot's product
                         Acc<V, NV> x = p;
                         // run heads: a slot whose left neighbour holds another row; the first
                         // slot past the valid ones counts as a head so that the last run ends there
