@@ -89,6 +89,26 @@ int da_spmm(int64_t m, int64_t k, int64_t N,
             const int32_t *rowptr, const int32_t *colind, const float *vals,
             const float *B, float *C, int algo, void *stream);
 
+/* Storage order of a dense operand. */
+enum { DA_ROW_MAJOR = 0, DA_COL_MAJOR = 1 };
+
+/*
+ * The same product with explicit storage order and leading dimension of B and C: the paper's
+ * literal N-loop axis (Sec. 3.3: X stored row- or column-major; "we have control on the
+ * intermediate matrix layout").  Element (r, n) of B is at B[r*ldb + n] for DA_ROW_MAJOR
+ * (ldb >= N) and at B[r + n*ldb] for DA_COL_MAJOR (ldb >= k); likewise C with ldc >= N or
+ * ldc >= m.  Everything else is as for da_spmm, which equals
+ * da_spmm_ex(..., B, N, DA_ROW_MAJOR, C, N, DA_ROW_MAJOR, ...).  Only the elements (r, n) with
+ * r < m (k for B), n < N are read or written; padding between rows / columns is left untouched.
+ * 16-byte accesses are used only for row-major operands whose leading dimensions are multiples
+ * of 4 and whose bases are 16-byte aligned; any other combination runs with 4-byte accesses.
+ * Returns DA_ERR_INVALID_ARG for an unknown layout or a leading dimension that is too small.
+ */
+int da_spmm_ex(int64_t m, int64_t k, int64_t N,
+               const int32_t *rowptr, const int32_t *colind, const float *vals,
+               const float *B, int64_t ldb, int layout_b,
+               float *C, int64_t ldc, int layout_c, int algo, void *stream);
+
 /*
  * Data-aware algorithm choice (Sec. 5.1): maps input characteristics to an algorithm id 0..7 by
  * walking a decision tree compiled into the library (trained offline on this GPU on seeded

@@ -7,6 +7,8 @@ Contents (each cites the passage of the paper it follows):
 
   spmm / spmm_rows        the definition Y = A.X in fp64 (Sec. 3.1, Fig. 2(a,b)); thin ctypes
                           marshalling over spmm_oracle.c, which holds the three loops
+  dense_view / spmm_ex    the same with X stored row- or column-major with a leading dimension
+                          (Sec. 3.3); pinned by explicit index loops on a tiny case
   features                input characteristics of Sec. 5.1, Table 2 (nnz, matrix size, standard
                           deviation of row lengths, N) plus mean / max row length
   conditional_reduction   the conditional prefix-sum network of Sec. 4 (EB+RM+PR, Fig. 6(e)),
@@ -108,6 +110,26 @@ def spmm_rows(rows, rowptr, colind, vals, B, want_abs: bool = True):
         _load().oracle_spmm_rows(rows.size, _p(rows), N, _p(rowptr), _p(colind), _p(vals), _p(B),
                                  _p(c), _p(s))
     return c, s
+
+
+def dense_view(buf, rows: int, cols: int, ld: int, col_major: bool):
+    """Logical rows x cols matrix stored in a flat buffer with leading dimension ld (Sec. 3.3: X kept
+    in row- or column-oriented order): element (r, c) is buf[r*ld + c] (row-major, ld >= cols) or
+    buf[r + c*ld] (column-major, ld >= rows).  Returns a view; padding is not part of it."""
+    buf = np.asarray(buf).reshape(-1)
+    if col_major:
+        if ld < rows:
+            raise ValueError("ld < rows")
+        return buf[: cols * ld].reshape(cols, ld)[:, :rows].T
+    if ld < cols:
+        raise ValueError("ld < cols")
+    return buf[: rows * ld].reshape(rows, ld)[:, :cols]
+
+
+def spmm_ex(rowptr, colind, vals, b_buf, k: int, N: int, ldb: int, b_col_major: bool, want_abs: bool = True):
+    """The definition of Sec. 3.1 with B given in either storage order: decodes the layout, then
+    runs the same three loops.  Returns logical m x N arrays (C_ref, S_abs)."""
+    return spmm(rowptr, colind, vals, np.ascontiguousarray(dense_view(b_buf, k, N, ldb, b_col_major)), want_abs)
 
 
 # --------------------------------------------------------------------------------------------

@@ -21,7 +21,8 @@ DA_OK, DA_ERR_INVALID_ARG, DA_ERR_BAD_ALGO, DA_ERR_UNSUPPORTED, DA_ERR_HIP = ran
 (DA_RB_RM_SR, DA_RB_RM_PR, DA_RB_CM_SR, DA_RB_CM_PR,
  DA_EB_RM_SR, DA_EB_RM_PR, DA_EB_CM_SR, DA_EB_CM_PR) = range(8)
 DA_NUM_ALGOS = 8
-EXPORTS = ("da_spmm", "da_spmm_select", "da_spmm_features", "da_spmm_algo_name", "da_spmm_last_error")
+DA_ROW_MAJOR, DA_COL_MAJOR = 0, 1
+EXPORTS = ("da_spmm", "da_spmm_ex", "da_spmm_select", "da_spmm_features", "da_spmm_algo_name", "da_spmm_last_error")
 
 
 class da_features(ctypes.Structure):
@@ -33,6 +34,9 @@ class da_features(ctypes.Structure):
 _vp, _i64 = ctypes.c_void_p, ctypes.c_int64
 _lib.da_spmm.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _vp]
 _lib.da_spmm.restype = ctypes.c_int
+_lib.da_spmm_ex.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _i64, ctypes.c_int, _vp, _i64, ctypes.c_int,
+                            ctypes.c_int, _vp]
+_lib.da_spmm_ex.restype = ctypes.c_int
 _lib.da_spmm_select.argtypes = [ctypes.POINTER(da_features)]
 _lib.da_spmm_select.restype = ctypes.c_int
 _lib.da_spmm_features.argtypes = [_i64, _i64, _vp, _vp, ctypes.POINTER(da_features)]
@@ -83,18 +87,34 @@ def da_spmm(m, k, N, rowptr, colind, vals, B, C, algo, stream=None) -> None:
         raise DaSpmmError(st, da_spmm_last_error())
 
 
+def da_spmm_ex_status(m, k, N, rowptr, colind, vals, B, ldb, layout_b, C, ldc, layout_c, algo, stream=None) -> int:
+    return int(_lib.da_spmm_ex(int(m), int(k), int(N), _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B), int(ldb),
+                               int(layout_b), _ptr(C), int(ldc), int(layout_c), int(algo), _stream(stream)))
+
+
+def da_spmm_ex(m, k, N, rowptr, colind, vals, B, ldb, layout_b, C, ldc, layout_c, algo, stream=None) -> None:
+    """C = A.B with explicit storage order (DA_ROW_MAJOR / DA_COL_MAJOR) and leading dimensions."""
+    st = da_spmm_ex_status(m, k, N, rowptr, colind, vals, B, ldb, layout_b, C, ldc, layout_c, algo, stream)
+    if st != DA_OK:
+        raise DaSpmmError(st, da_spmm_last_error())
+
+
 class PreparedSpmm:
     """The same call with its arguments marshalled once: `run = PreparedSpmm(m, k, N, rowptr, colind,
     vals, B, C, stream); run(algo)`.  Saves the per-call conversion cost (about 4 us in CPython),
     which matters when the product itself takes a few microseconds.  The tensors must stay alive and
     the stream is the one current when the object was made (or the one given)."""
 
-    def __init__(self, m, k, N, rowptr, colind, vals, B, C, stream=None):
+    def __init__(self, m, k, N, rowptr, colind, vals, B, C, stream=None, ldb=None, layout_b=DA_ROW_MAJOR,
+                 ldc=None, layout_c=DA_ROW_MAJOR):
         self._keep = (rowptr, colind, vals, B, C)
+        ldb = (N if layout_b == DA_ROW_MAJOR else k) if ldb is None else ldb
+        ldc = (N if layout_c == DA_ROW_MAJOR else m) if ldc is None else ldc
         self._args = (_i64(int(m)), _i64(int(k)), _i64(int(N)), _vp(_ptr(rowptr)), _vp(_ptr(colind)),
-                      _vp(_ptr(vals)), _vp(_ptr(B)), _vp(_ptr(C)))
+                      _vp(_ptr(vals)), _vp(_ptr(B)), _i64(int(ldb)), ctypes.c_int(int(layout_b)),
+                      _vp(_ptr(C)), _i64(int(ldc)), ctypes.c_int(int(layout_c)))
         self._stream = _vp(_stream(stream))
-        self._fn = _lib.da_spmm
+        self._fn = _lib.da_spmm_ex
 
     def __call__(self, algo: int) -> None:
         st = self._fn(*self._args, algo, self._stream)

@@ -26,7 +26,8 @@ RM, CM = (0, 1, 4, 5), (2, 3, 6, 7)
 SR, PR = (0, 2, 4, 6), (1, 3, 5, 7)
 
 
-def time_all(a, N):
+def time_all(a, N, col_major=False):
+    """Times of the 8 ids; with col_major both B and C are stored column-major (da_spmm_ex)."""
     dev = torch.device("cuda:0")
     rp, ci, va = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals))
     da.da_spmm_features(a.m, N, rp)
@@ -34,7 +35,8 @@ def time_all(a, N):
     g.manual_seed(a.seed * 1000 + N)
     Bs = [torch.empty((a.k, N), device=dev).uniform_(-1.0, 1.0, generator=g) for _ in range(COPIES)]
     Cs = [torch.empty((a.m, N), device=dev) for _ in range(COPIES)]
-    runs = [da.PreparedSpmm(a.m, a.k, N, rp, ci, va, Bs[i], Cs[i]) for i in range(COPIES)]
+    lay = da.DA_COL_MAJOR if col_major else da.DA_ROW_MAJOR     # the buffers are just reinterpreted
+    runs = [da.PreparedSpmm(a.m, a.k, N, rp, ci, va, Bs[i], Cs[i], layout_b=lay, layout_c=lay) for i in range(COPIES)]
     times = []
     for algo in range(da.DA_NUM_ALGOS):
         t, _ = time_algo(lambda i, algo=algo: runs[i % COPIES](algo))
@@ -65,6 +67,12 @@ def main():
     m = gen.rmat_csr(17, 16.0, 0.45, 0.22, 0.22, seed=8210)
     for N in (2, 4, 8, 32, 128):
         line(f"  N = {N}", time_all(m, N), RM, CM, "RM", "CM")
+    print("stored layouts (Sec. 3.3 literally): same matrix, best of the 8 ids with B and C row-major against column-major")
+    for N in (2, 4, 8, 32, 128):
+        tr, tc = time_all(m, N), time_all(m, N, col_major=True)
+        ir, ic = int(np.argmin(tr)), int(np.argmin(tc))
+        print(f"  N = {N:3d}   row-major {tr[ir]:9.1f} us ({da.ALGO_NAMES[ir]})   column-major {tc[ic]:9.1f} us ({da.ALGO_NAMES[ic]})"
+              f"   row/column time ratio {tr[ir] / tc[ic]:6.2f}", flush=True)
     print("SR-PR: R-MAT (a,b,c)=(0.45,0.22,0.22), 16 entries per row, N = 32")
     for i, scale in enumerate((10, 12, 14, 17, 20)):
         m = gen.rmat_csr(scale, 16.0, 0.45, 0.22, 0.22, seed=8220 + i)

@@ -49,6 +49,7 @@ int pow2_ceil(long x) {
 
 struct Problem {
     int m, N;
+    Strides sd;
     const int* rowptr;
     const int* colind;
     const float* vals;
@@ -105,10 +106,12 @@ int64_t lookup_nnz(const void* rowptr, int64_t m) {
 // run at full rate, 8-byte gathers at about half, and narrow rows (N < 32) gather fastest with one
 // column per lane.  Setting DA_SPMM_TUNE=1 lets DA_SPMM_V / _G / _NV / _CHUNK override the choice
 // (for tuning runs only; invalid combinations are rejected).
-int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const void* C, int64_t known_nnz,
-                  Geometry* out) {
+int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const void* C, const Strides& sd,
+                  int64_t known_nnz, Geometry* out) {
     const uintptr_t addr = reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C);
-    const bool vec4_ok = (N % 4 == 0) && (addr % 16 == 0);
+    // 16-byte accesses need unit column strides and rows that start on 16-byte boundaries
+    const bool vec4_ok = (N % 4 == 0) && (addr % 16 == 0) && sd.cb == 1 && sd.cc == 1 &&
+                         sd.rb % 4 == 0 && sd.rc % 4 == 0;
     Geometry g{1, 1, 1, 0, false};
     if (cm) {
         g.V = vec4_ok ? 4 : 1;
@@ -172,13 +175,13 @@ int launch(Family fam, const Problem& p, const Geometry& geo) {
     case RB_SR: {
         const long rows_per_block = (long)kWavesPerBlock * (kWave / G);
         hipLaunchKernelGGL((rb_sr_kernel<V, G, NV>), grid_for((p.m + rows_per_block - 1) / rows_per_block),
-                           block, 0, p.stream, p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, pin);
+                           block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, pin);
         break;
     }
     case RB_PR: {
         if constexpr (G <= kMaxGroupPR) {
             hipLaunchKernelGGL((rb_pr_kernel<V, G, NV>), grid_for((p.m + kWavesPerBlock - 1) / kWavesPerBlock),
-                               block, 0, p.stream, p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, pin);
+                               block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, pin);
         }
         break;
     }
@@ -206,14 +209,14 @@ int launch(Family fam, const Problem& p, const Geometry& geo) {
         if (blocks < 1) blocks = 1;
         // pre-pass: zero the rows that receive atomic additions, and the rows without entries
         const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
-        hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.rowptr, p.C, chunk);
+        hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.C, chunk);
         if (fam == EB_SR) {
             hipLaunchKernelGGL((eb_sr_kernel<V, G, NV>), grid_for(blocks), block, 0, p.stream,
-                               p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin);
+                               p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin);
         } else {
             if constexpr (G <= kMaxGroupPR)
                 hipLaunchKernelGGL((eb_pr_kernel<V, G, NV>), grid_for(blocks), block, 0, p.stream,
-                                   p.m, p.N, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin);
+                                   p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin);
         }
         break;
     }
@@ -257,27 +260,44 @@ const char* const kNames[DA_NUM_ALGOS] = {
 
 extern "C" {
 
-int da_spmm(int64_t m, int64_t k, int64_t N, const int32_t* rowptr, const int32_t* colind,
-            const float* vals, const float* B, float* C, int algo, void* stream)
+int da_spmm_ex(int64_t m, int64_t k, int64_t N, const int32_t* rowptr, const int32_t* colind,
+               const float* vals, const float* B, int64_t ldb, int layout_b, float* C, int64_t ldc,
+               int layout_c, int algo, void* stream)
 {
     if (m < 0 || k < 0 || N < 0) return fail(DA_ERR_INVALID_ARG, "negative size%s");
     if (m > 0x7ffffffeLL || k > 0x7fffffffLL || N > 0x7fffffffLL)
         return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
     if (algo < 0 || algo >= DA_NUM_ALGOS) return fail(DA_ERR_BAD_ALGO, "algorithm id outside 0..7%s");
+    if ((layout_b != DA_ROW_MAJOR && layout_b != DA_COL_MAJOR) || (layout_c != DA_ROW_MAJOR && layout_c != DA_COL_MAJOR))
+        return fail(DA_ERR_INVALID_ARG, "layout is neither DA_ROW_MAJOR nor DA_COL_MAJOR%s");
+    if (ldb < (layout_b == DA_ROW_MAJOR ? N : k) || ldc < (layout_c == DA_ROW_MAJOR ? N : m))
+        return fail(DA_ERR_INVALID_ARG, "leading dimension smaller than the extent it strides over%s");
     if (m == 0 || N == 0) return DA_OK;
     if (!rowptr || !C) return fail(DA_ERR_INVALID_ARG, "null rowptr or C%s");
     // colind, vals and B are read only through stored entries; they may be null when nnz == 0,
     // which only the device knows
 
-    Problem p{(int)m, (int)N, rowptr, colind, vals, B, C, (hipStream_t)stream, k};
+    Strides sd;
+    sd.rb = layout_b == DA_ROW_MAJOR ? ldb : 1;
+    sd.cb = layout_b == DA_ROW_MAJOR ? 1 : ldb;
+    sd.rc = layout_c == DA_ROW_MAJOR ? ldc : 1;
+    sd.cc = layout_c == DA_ROW_MAJOR ? 1 : ldc;
+    Problem p{(int)m, (int)N, sd, rowptr, colind, vals, B, C, (hipStream_t)stream, k};
     const bool eb = algo >= DA_EB_RM_SR;
     const bool cm = (algo & 2) != 0;
     const bool pr = (algo & 1) != 0;
     Geometry g;
-    const int st = pick_geometry(cm, pr, eb, N, B, C, eb ? lookup_nnz(rowptr, m) : -1, &g);
+    const int st = pick_geometry(cm, pr, eb, N, B, C, sd, eb ? lookup_nnz(rowptr, m) : -1, &g);
     if (st != DA_OK) return st;
     const Family fam = eb ? (pr ? EB_PR : EB_SR) : (pr ? RB_PR : RB_SR);
     return dispatch(fam, g, p);
+}
+
+int da_spmm(int64_t m, int64_t k, int64_t N, const int32_t* rowptr, const int32_t* colind,
+            const float* vals, const float* B, float* C, int algo, void* stream)
+{
+    if (N < 0) return fail(DA_ERR_INVALID_ARG, "negative size%s");
+    return da_spmm_ex(m, k, N, rowptr, colind, vals, B, N, DA_ROW_MAJOR, C, N, DA_ROW_MAJOR, algo, stream);
 }
 
 int da_spmm_features(int64_t m, int64_t N, const int32_t* rowptr, void* stream, da_features* out)

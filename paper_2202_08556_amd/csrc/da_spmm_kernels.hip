@@ -33,6 +33,13 @@ constexpr int kBlock = 256;                 // 4 waves
 constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kU = 8;                       // gathers in flight per lane
 
+// Element strides of the dense operands: B(r, n) is at B[r*rb + n*cb], C(i, n) at C[i*rc + n*cc].
+// Row-major storage has cb = cc = 1 and rb, rc = leading dimension; column-major storage has
+// rb = rc = 1 and cb, cc = leading dimension.  Vector loads / stores (V = 4) need cb = cc = 1.
+struct Strides {
+    long rb, cb, rc, cc;
+};
+
 // ------------------------------------------------------------------------------------------
 // small helpers
 // ------------------------------------------------------------------------------------------
@@ -84,10 +91,10 @@ struct Acc {
             for (int v = 0; v < V; ++v) a[i][v] = 0.f;
     }
     // Branch-free gather of the lane's vectors of one B row (nvalid >= 1).  Vectors past nvalid
-    // re-read vector 0 (valid memory); their values are never written out.
-    __device__ __forceinline__ void load(const float* __restrict__ p, int nvalid) {
+    // re-read vector 0 (valid memory); their values are never written out.  cs = column stride.
+    __device__ __forceinline__ void load(const float* __restrict__ p, int nvalid, long cs) {
 #pragma unroll
-        for (int i = 0; i < NV; ++i) load_vec<V>(p + (i < nvalid ? i : 0) * V, a[i]);
+        for (int i = 0; i < NV; ++i) load_vec<V>(p + (i < nvalid ? i : 0) * V * cs, a[i]);
     }
     __device__ __forceinline__ void fma(float s, const Acc& b) {
 #pragma unroll
@@ -107,10 +114,10 @@ struct Acc {
 #pragma unroll
             for (int v = 0; v < V; ++v) a[i][v] += b.a[i][v];
     }
-    __device__ __forceinline__ void emit(float* __restrict__ p, int nvalid, bool atomic) const {
+    __device__ __forceinline__ void emit(float* __restrict__ p, int nvalid, bool atomic, long cs) const {
 #pragma unroll
         for (int i = 0; i < NV; ++i)
-            if (i < nvalid) emit_vec<V>(p + i * V, a[i], atomic);
+            if (i < nvalid) emit_vec<V>(p + i * V * cs, a[i], atomic);
     }
 };
 
@@ -255,7 +262,7 @@ __device__ __forceinline__ void for_blocks(int cnt, F&& f) {
 // ------------------------------------------------------------------------------------------
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
-    int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
+    int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int pin_tiles)
 {
     constexpr int RPW = kWave / G;                       // rows per wave
@@ -272,7 +279,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
     if (row < m) { start = rowptr[row]; end = rowptr[row + 1]; }
     Acc<V, NV> acc;
     acc.clear();
-    const float* __restrict__ Bn = B + n0;
+    const float* __restrict__ Bn = B + (long)n0 * sd.cb;
 
     if constexpr (G == 1) {
         if (nvec > 0) {
@@ -285,7 +292,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
 #pragma unroll
                 for (int u = 0; u < UU; ++u) { c[u] = colind[p0 + u]; a[u] = vals[p0 + u]; }
 #pragma unroll
-                for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)c[u] * N, nvec);
+                for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)c[u] * sd.rb, nvec, sd.cb);
 #pragma unroll
                 for (int u = 0; u < UU; ++u) acc.fma(a[u], b[u]);
             });
@@ -306,7 +313,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
 #pragma unroll
                     for (int u = 0; u < UU; ++u) e[u] = st[t + u];
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * N, nvec);
+                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * sd.rb, nvec, sd.cb);
 #pragma unroll
                     for (int u = 0; u < UU; ++u) acc.fma(__int_as_float(e[u].y), b[u]);
                 });
@@ -314,7 +321,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
             wave_lds_sync();
         }
     }
-    if (row < m && nvec > 0) acc.emit(C + row * N + n0, nvec, false);
+    if (row < m && nvec > 0) acc.emit(C + row * sd.rc + (long)n0 * sd.cc, nvec, false, sd.cc);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -326,7 +333,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
 // ------------------------------------------------------------------------------------------
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
-    int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
+    int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int pin_tiles)
 {
     constexpr int S = kWave / G;
@@ -342,7 +349,7 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
     const int start = rowptr[row], end = rowptr[row + 1];
     Acc<V, NV> acc;
     acc.clear();
-    const float* __restrict__ Bn = B + n0;
+    const float* __restrict__ Bn = B + (long)n0 * sd.cb;
 
     if constexpr (G == 1) {
         if (nvec > 0) {
@@ -357,14 +364,14 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 #pragma unroll
                 for (int u = 0; u < UU; ++u) { c[u] = colind[p0 + u * kWave]; a[u] = vals[p0 + u * kWave]; }
 #pragma unroll
-                for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)c[u] * N, nvec);
+                for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)c[u] * sd.rb, nvec, sd.cb);
 #pragma unroll
                 for (int u = 0; u < UU; ++u) acc.fma(a[u], b[u]);
             });
             const int p = start + (len / kWave) * kWave + lane;
             if (p < end) {
                 Acc<V, NV> b;
-                b.load(Bn + (long)colind[p] * N, nvec);
+                b.load(Bn + (long)colind[p] * sd.rb, nvec, sd.cb);
                 acc.fma(vals[p], b);
             }
         }
@@ -385,7 +392,7 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 #pragma unroll
                     for (int u = 0; u < UU; ++u) ee[u] = st[(t + u) * S + s];
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)ee[u].x * N, nvec);
+                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)ee[u].x * sd.rb, nvec, sd.cb);
 #pragma unroll
                     for (int u = 0; u < UU; ++u) acc.fma(__int_as_float(ee[u].y), b[u]);
                 });
@@ -393,7 +400,7 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
                 if (t < cnt) {
                     const int2 ee = st[t];
                     Acc<V, NV> b;
-                    b.load(Bn + (long)ee.x * N, nvec);
+                    b.load(Bn + (long)ee.x * sd.rb, nvec, sd.cb);
                     acc.fma(__int_as_float(ee.y), b);
                 }
             }
@@ -405,7 +412,7 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
     for (int i = 0; i < NV; ++i)
 #pragma unroll
         for (int v = 0; v < V; ++v) acc.a[i][v] = slot_allreduce<G>(acc.a[i][v]);
-    if (s == 0 && nvec > 0) acc.emit(C + row * N + n0, nvec, false);
+    if (s == 0 && nvec > 0) acc.emit(C + row * sd.rc + (long)n0 * sd.cc, nvec, false, sd.cc);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -419,7 +426,7 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 // ------------------------------------------------------------------------------------------
 template <int V>
 __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
-    int m, int N, const int* __restrict__ rowptr, float* __restrict__ C, int chunk)
+    int m, int N, Strides sd, const int* __restrict__ rowptr, float* __restrict__ C, int chunk)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long base = ((long)blockIdx.x * kWavesPerBlock + wave) * kWave;
@@ -437,8 +444,8 @@ __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
     while (mask) {
         const int r = __ffsll((long long)mask) - 1;
         mask &= mask - 1;
-        float* __restrict__ crow = C + (base + r) * N;
-        for (int n0 = lane * V; n0 < N; n0 += kWave * V) store_vec<V>(crow + n0, z);
+        float* __restrict__ crow = C + (base + r) * sd.rc;
+        for (int n0 = lane * V; n0 < N; n0 += kWave * V) store_vec<V>(crow + (long)n0 * sd.cc, z);
     }
 }
 
@@ -453,7 +460,7 @@ __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
 // ------------------------------------------------------------------------------------------
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
-    int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
+    int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
     int pin_tiles)
 {
@@ -466,8 +473,8 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     const BlockMap bm = block_map(pin_tiles);
     const int n0 = (bm.tile * G + j) * V * NV;
     const int nvec = valid_vectors<V, NV>(n0, N);
-    const float* __restrict__ Bn = B + n0;
-    float* __restrict__ Cn = C + n0;
+    const float* __restrict__ Bn = B + (long)n0 * sd.cb;
+    float* __restrict__ Cn = C + (long)n0 * sd.cc;
     const int nnz = rowptr[m];
     const long nworkers = bm.nbx * kWavesPerBlock * GPW;
     const long worker = (bm.bx * kWavesPerBlock + wave) * GPW + g;
@@ -501,7 +508,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
                 }
                 if (nvec > 0) {
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * N, nvec);
+                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * sd.rb, nvec, sd.cb);
                 }
                 if (row_end > q0 + t + UU) {
                     // the common case: the whole block lies inside the current row
@@ -523,7 +530,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
                         if (nvec > 0) acc.add(b[u]);
                         const int next = q0 + t + u + 1;
                         if (next == row_end) {                 // the row is complete
-                            if (nvec > 0) acc.emit(Cn + (long)row * N, nvec, shared_with_prev);
+                            if (nvec > 0) acc.emit(Cn + (long)row * sd.rc, nvec, shared_with_prev, sd.cc);
                             acc.clear();
                             shared_with_prev = false;
                             if (next < c1) {
@@ -536,7 +543,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
             if constexpr (G > 1) wave_lds_sync();
         }
         if (row_end > c1 && nvec > 0)                      // last row continues in the next chunk
-            acc.emit(Cn + (long)row * N, nvec, true);
+            acc.emit(Cn + (long)row * sd.rc, nvec, true, sd.cc);
     }
 }
 
@@ -570,7 +577,7 @@ __device__ __forceinline__ Acc<V, NV> slots_allreduce(Acc<V, NV> x) {
 
 template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
-    int m, int N, const int* __restrict__ rowptr, const int* __restrict__ colind,
+    int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
     int pin_tiles)
 {
@@ -582,8 +589,8 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     const BlockMap bm = block_map(pin_tiles);
     const int n0 = (bm.tile * G + j) * V * NV;
     const int nvec = valid_vectors<V, NV>(n0, N);
-    const float* __restrict__ Bn = B + n0;
-    float* __restrict__ Cn = C + n0;
+    const float* __restrict__ Bn = B + (long)n0 * sd.cb;
+    float* __restrict__ Cn = C + (long)n0 * sd.cc;
     const int nnz = rowptr[m];
     const long nwaves = bm.nbx * kWavesPerBlock;
     const long wave_id = bm.bx * kWavesPerBlock + wave;
@@ -628,7 +635,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                 // branch-free gathers: slots past the end of the chunk hold column 0
                 if (nvec > 0) {
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * N, nvec);
+                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * sd.rb, nvec, sd.cb);
                 }
                 // all products first: no store or atomic is issued while a gather is outstanding
                 // (stores share the in-order memory counter with loads)
@@ -659,7 +666,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                         acc.add(b[u]);
                         if (last_flags & 2) {                           // the row ends here
                             const Acc<V, NV> total = slots_allreduce<V, G, NV>(acc);
-                            if (s == 0 && nvec > 0) total.emit(Cn + (long)cur * N, nvec, !cur_started);
+                            if (s == 0 && nvec > 0) total.emit(Cn + (long)cur * sd.rc, nvec, !cur_started, sd.cc);
                             acc.clear();
                             cur = -1;
                         }
@@ -700,7 +707,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                         const bool last_ended = (last_flags & 2) != 0;
                         const bool in_last_run = evalid && er == last_row;
                         if (head && evalid && nvec > 0 && (!in_last_run || last_ended))
-                            x.emit(Cn + (long)er * N, nvec, !started);
+                            x.emit(Cn + (long)er * sd.rc, nvec, !started, sd.cc);
                         if (last_ended) {
                             acc.clear();
                             cur = -1;
@@ -719,7 +726,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
         }
         if (cur >= 0) {                                       // row continues in the next chunk
             const Acc<V, NV> total = slots_allreduce<V, G, NV>(acc);
-            if (s == 0 && nvec > 0) total.emit(Cn + (long)cur * N, nvec, true);
+            if (s == 0 && nvec > 0) total.emit(Cn + (long)cur * sd.rc, nvec, true, sd.cc);
         }
     }
 }

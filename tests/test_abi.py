@@ -53,6 +53,18 @@ def test_argument_errors_without_device_work():
         da.da_spmm(4, 4, 4, None, None, None, None, None, 0, stream=0)
 
 
+def test_ex_argument_errors_without_device_work():
+    f = da.da_spmm_ex_status
+    R, Cm = da.DA_ROW_MAJOR, da.DA_COL_MAJOR
+    assert f(4, 6, 8, 0, 0, 0, 0, 8, 2, 0, 8, R, 0, stream=0) == da.DA_ERR_INVALID_ARG      # unknown layout
+    assert f(4, 6, 8, 0, 0, 0, 0, 7, R, 0, 8, R, 0, stream=0) == da.DA_ERR_INVALID_ARG      # ldb < N
+    assert f(4, 6, 8, 0, 0, 0, 0, 5, Cm, 0, 8, R, 0, stream=0) == da.DA_ERR_INVALID_ARG     # ldb < k
+    assert f(4, 6, 8, 0, 0, 0, 0, 8, R, 0, 3, Cm, 0, stream=0) == da.DA_ERR_INVALID_ARG     # ldc < m
+    assert "leading dimension" in da.da_spmm_last_error()
+    assert f(0, 6, 8, None, None, None, None, 8, R, None, 8, R, 0, stream=0) == da.DA_OK
+    assert f(4, 6, 8, None, None, None, None, 8, R, None, 8, R, 9, stream=0) == da.DA_ERR_BAD_ALGO
+
+
 def feats(rows, mean, cv, mx, N):
     return dict(rows=rows, nnz=int(rows * mean), row_nnz_mean=mean, row_nnz_std=cv * mean,
                 row_nnz_max=mx, N=N)

@@ -236,3 +236,33 @@ def test_calls_can_be_captured_in_a_hip_graph(gpu):
         for algo in ALGOS:
             r = orc.tolerance_ratio(outs[algo].cpu().numpy(), c_ref, s_abs)
             assert r <= 1.0, f"replay {replay} algo {algo}: {r}"
+
+
+@pytest.mark.parametrize("b_col,c_col", [(False, False), (True, False), (False, True), (True, True)])
+def test_storage_orders_and_leading_dimensions(gpu, b_col, c_col):
+    """da_spmm_ex: every algorithm id with B and C row- or column-major and padded leading
+    dimensions; padding of C must stay untouched."""
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    a = gen.skewed_csr(m=1500, k=1100, heavy_frac=0.004, heavy_lo=400, heavy_hi=900, seed=31)
+    rp, ci, va = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals))
+    for N, pad in ((8, 0), (36, 4), (5, 3)):
+        ldb = (a.k if b_col else N) + pad
+        ldc = (a.m if c_col else N) + pad
+        logical = gen.dense(a.k, N, "uniform", seed=32 + N)
+        b_host = np.full((N if b_col else a.k) * ldb, 7.0, dtype=np.float32)
+        orc.dense_view(b_host, a.k, N, ldb, b_col)[...] = logical
+        c_ref, s_abs = orc.spmm_ex(a.rowptr, a.colind, a.vals, b_host, a.k, N, ldb, b_col)
+        Bd = torch.from_numpy(b_host).to(dev)
+        for algo in ALGOS:
+            print(f"layouts B{'C' if b_col else 'R'} C{'C' if c_col else 'R'} N={N} algo={algo}", flush=True)
+            Cd = torch.full(((N if c_col else a.m) * ldc,), -5.0, device=dev)
+            da.da_spmm_ex(a.m, a.k, N, rp, ci, va, Bd, ldb, int(b_col), Cd, ldc, int(c_col), algo)
+            torch.cuda.synchronize()
+            c_host = Cd.cpu().numpy()
+            got = orc.dense_view(c_host, a.m, N, ldc, c_col)
+            assert orc.tolerance_ratio(got, c_ref, s_abs) <= 1.0
+            mask = np.ones(c_host.size, dtype=bool)
+            idx = np.arange(c_host.size).reshape(-1)
+            orc.dense_view(mask, a.m, N, ldc, c_col)[...] = False
+            assert np.all(c_host[mask] == -5.0), "padding of C was written"

@@ -309,3 +309,20 @@ def test_tolerance_ratio_and_bit_mismatches():
     z = np.array([-0.0, 3.0], dtype=np.float32)
     assert orc.bit_mismatches(z, np.array([0.0, 3.0])) == 0
     assert orc.bit_mismatches(z, np.array([0.0, 3.0000002])) == 1
+
+
+# storage orders (Sec. 3.3) ---------------------------------------------------------------------
+def test_dense_view_and_spmm_ex_against_explicit_index_loops():
+    k, N = 5, 3
+    a = gen.uniform_csr(m=7, k=k, mean_len=2, seed=95)
+    logical = gen.dense_int(k, N, seed=96)
+    for col_major, ld in ((False, 3), (False, 5), (True, 5), (True, 8)):
+        buf = np.full((N if col_major else k) * ld + 2, 99.0, dtype=np.float32)     # padding = 99
+        for r in range(k):
+            for n in range(N):
+                buf[(r + n * ld) if col_major else (r * ld + n)] = logical[r, n]
+        assert np.array_equal(orc.dense_view(buf, k, N, ld, col_major), logical)
+        c, _ = orc.spmm_ex(a.rowptr, a.colind, a.vals, buf, k, N, ld, col_major)
+        np.testing.assert_array_equal(c, dense_of(a) @ logical.astype(np.float64))
+    with pytest.raises(ValueError):
+        orc.dense_view(np.zeros(100), k, N, 2, False)
