@@ -9,6 +9,10 @@ Contents (each cites the passage of the paper it follows):
                           marshalling over spmm_oracle.c, which holds the three loops
   dense_view / spmm_ex    the same with X stored row- or column-major with a leading dimension
                           (Sec. 3.3); pinned by explicit index loops on a tiny case
+  spmm_transposed         A^T.G from the definition (scatter over A's own entries): the backward
+                          pass of the aggregation step of a graph-convolution layer (Sec. 6, GCN)
+  csr_transpose           CSR arrays of A^T with ascending indices inside every row
+  gcn_layer / gcn_layer_backward   relu(A.(X.W) + b) and its gradients in fp64 (Sec. 6, GCN)
   features                input characteristics of Sec. 5.1, Table 2 (nnz, matrix size, standard
                           deviation of row lengths, N) plus mean / max row length
   conditional_reduction   the conditional prefix-sum network of Sec. 4 (EB+RM+PR, Fig. 6(e)),
@@ -23,7 +27,9 @@ normalised adjacency times ones; 27-point stencil neighbour counts), linearity a
 independence, entry permutation / splitting, scipy's CSR product, and a literal pure-Python triple
 loop.  conditional_reduction is pinned against per-run sums computed by a scalar loop and by the
 paper's validity rule on the 6/2/0/3/1 example; normalized_performance against hand-computed
-two-input examples.
+two-input examples.  spmm_transposed / csr_transpose: dense transposes of tiny matrices built by index
+loops, scipy's conversion, transposing twice, the structural symmetry of the stencil, and central
+differences of <G, A.X>; gcn_layer_backward: central differences of the fp64 forward pass.
 """
 from __future__ import annotations
 
@@ -59,6 +65,8 @@ def _load():
         lib.oracle_spmm.restype = None
         lib.oracle_spmm_rows.argtypes = [i64, vp, i64, vp, vp, vp, vp, vp, vp]
         lib.oracle_spmm_rows.restype = None
+        lib.oracle_spmm_transposed.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp]
+        lib.oracle_spmm_transposed.restype = None
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -130,6 +138,78 @@ def spmm_ex(rowptr, colind, vals, b_buf, k: int, N: int, ldb: int, b_col_major: 
     """The definition of Sec. 3.1 with B given in either storage order: decodes the layout, then
     runs the same three loops.  Returns logical m x N arrays (C_ref, S_abs)."""
     return spmm(rowptr, colind, vals, np.ascontiguousarray(dense_view(b_buf, k, N, ldb, b_col_major)), want_abs)
+
+
+# --------------------------------------------------------------------------------------------
+# transposed product, transposed structure and the graph-convolution layer (Sec. 6, GCN)
+# --------------------------------------------------------------------------------------------
+def spmm_transposed(rowptr, colind, vals, G, k: int, want_abs: bool = True):
+    """(D_ref, S_abs) as fp64 k x N arrays with D = A^T.G, where A is m x k and G is m x N: every
+    stored entry (i, j) adds vals * G[i, :] to row j.  Gradient of <G, A.X> with respect to X."""
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    G = np.ascontiguousarray(G, dtype=np.float32)
+    m = rowptr.size - 1
+    if G.ndim != 2 or G.shape[0] != m:
+        raise ValueError("G must be m x N")
+    if colind.size and (colind.min() < 0 or colind.max() >= k):
+        raise ValueError("column index outside [0, k)")
+    N = G.shape[1]
+    d = np.zeros((k, N), dtype=np.float64)
+    s = np.zeros((k, N), dtype=np.float64) if want_abs else None
+    if k and N:
+        _load().oracle_spmm_transposed(m, k, N, _p(rowptr), _p(colind), _p(vals), _p(G), _p(d), _p(s))
+    return d, s
+
+
+def csr_transpose(rowptr, colind, vals, k: int):
+    """CSR arrays (t_rowptr int32[k+1], t_colind int32[nnz], t_vals fp32[nnz]) of A^T for an m x k
+    matrix A: row j of A^T lists the entries of column j of A with their row numbers ascending (ties,
+    i.e. repeated (i, j) entries, keep their stored order).  A stable sort of the entries by column
+    is exactly that, because CSR already stores them row after row."""
+    rowptr = np.asarray(rowptr, dtype=np.int64)
+    colind = np.asarray(colind, dtype=np.int64)
+    vals = np.asarray(vals, dtype=np.float32)
+    m = rowptr.size - 1
+    row_of_entry = np.repeat(np.arange(m, dtype=np.int64), np.diff(rowptr))
+    order = np.argsort(colind, kind="stable")
+    t_rowptr = np.zeros(k + 1, dtype=np.int64)
+    t_rowptr[1:] = np.cumsum(np.bincount(colind, minlength=k))
+    return t_rowptr.astype(np.int32), row_of_entry[order].astype(np.int32), vals[order].copy()
+
+
+def gcn_layer(rowptr, colind, vals, X, W, bias=None, relu: bool = True):
+    """One graph-convolution layer in fp64: Z = A.(X.W) + b, output relu(Z) (or Z).  A is the
+    (normalised) adjacency matrix in CSR, X the m x F_in node features, W F_in x F_out.  Returns
+    (output, Z)."""
+    H = np.asarray(X, dtype=np.float64) @ np.asarray(W, dtype=np.float64)
+    rp = np.asarray(rowptr, dtype=np.int64)
+    ci = np.asarray(colind, dtype=np.int64)
+    va = np.asarray(vals, dtype=np.float64)
+    Z = np.zeros((rp.size - 1, H.shape[1]), dtype=np.float64)
+    for i in range(rp.size - 1):
+        seg = slice(rp[i], rp[i + 1])
+        Z[i] = va[seg] @ H[ci[seg]]
+    if bias is not None:
+        Z = Z + np.asarray(bias, dtype=np.float64)
+    return (np.maximum(Z, 0.0) if relu else Z), Z
+
+
+def gcn_layer_backward(rowptr, colind, vals, X, W, Z, d_out, relu: bool = True):
+    """Gradients of sum(d_out * layer output) in fp64: with dZ = d_out masked by Z > 0,
+    dH = A^T.dZ, dX = dH.W^T, dW = X^T.dH, db = column sums of dZ.  Returns (dX, dW, db)."""
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    dZ = np.asarray(d_out, dtype=np.float64) * ((Z > 0.0) if relu else 1.0)
+    rp = np.asarray(rowptr, dtype=np.int64)
+    ci = np.asarray(colind, dtype=np.int64)
+    va = np.asarray(vals, dtype=np.float64)
+    dH = np.zeros((X.shape[0], W.shape[1]), dtype=np.float64)
+    for i in range(rp.size - 1):
+        for p in range(rp[i], rp[i + 1]):
+            dH[ci[p]] += va[p] * dZ[i]
+    return dH @ W.T, X.T @ dH, dZ.sum(axis=0)
 
 
 # --------------------------------------------------------------------------------------------

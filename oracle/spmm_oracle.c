@@ -71,3 +71,32 @@ void oracle_spmm_rows(int64_t nrows, const int64_t *rows, int64_t N, const int32
     for (int64_t t = 0; t < nrows; ++t)
         one_row(rows[t], N, rowptr, colind, vals, B, c_ref + t * N, s_abs ? s_abs + t * N : 0);
 }
+
+/*
+ * Product with the transposed matrix, straight from the definition (A^T)[j][i] = A[i][j]:
+ *     D[j][n] = sum over stored entries (i, j) of A   (double)vals[p] * (double)G[i*N + n]
+ * This is the gradient of  <G, A*X>  with respect to X (the backward pass of the aggregation step of
+ * a graph-convolution layer, the application of Sec. 6's GCN experiment).  The loops walk A in its
+ * own CSR order and scatter into row colind[p] of the output, so no transposed structure is built;
+ * serial, because different rows of A add into the same output row.  d_ref, s_abs: k x N doubles,
+ * overwritten (s_abs may be NULL).
+ */
+void oracle_spmm_transposed(int64_t m, int64_t k, int64_t N, const int32_t *rowptr,
+                            const int32_t *colind, const float *vals, const float *G,
+                            double *d_ref, double *s_abs)
+{
+    for (int64_t t = 0; t < k * N; ++t) {
+        d_ref[t] = 0.0;
+        if (s_abs) s_abs[t] = 0.0;
+    }
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            double a = (double)vals[p];
+            int64_t j = colind[p];
+            for (int64_t n = 0; n < N; ++n) {
+                double g = (double)G[i * N + n];
+                d_ref[j * N + n] += a * g;
+                if (s_abs) s_abs[j * N + n] += fabs(a) * fabs(g);
+            }
+        }
+}
