@@ -22,6 +22,7 @@
 #ifndef DA_SPMM_H
 #define DA_SPMM_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -128,6 +129,31 @@ int da_spmm_select(const da_features *f);
  * stored entry whatever the grid size).
  */
 int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, da_features *out);
+
+/*
+ * CSR arrays of the transpose.  The paper's GCN experiment (Sec. 6) runs the SpMM inside a graph
+ * neural network layer; training such a layer needs the gradient of <G, A*X> with respect to X,
+ * which is A^T * G -- the same sparse-times-dense product on the transposed matrix.  This call
+ * builds A^T once per graph so that da_spmm (and the selector) serve the backward pass too.
+ *
+ *   A        m x k, CSR: rowptr int32[m+1], colind int32[nnz] (each in [0, k)), vals fp32[nnz];
+ *            nnz is passed by the caller and must equal rowptr[m]
+ *   A^T      k x m, CSR: t_rowptr int32[k+1], t_colind int32[nnz], t_vals fp32[nnz], written by
+ *            the call; inside every row of A^T the indices ascend (entries of equal (row, column)
+ *            keep their stored order), so the result is deterministic bit for bit
+ *   workspace  device scratch of at least the size da_csr_transpose_workspace reports for the
+ *            same (m, k, nnz), 256-byte aligned, owned by the caller, free for reuse once the
+ *            stream has passed the call; may be NULL when nnz == 0
+ * The call allocates nothing, only enqueues kernels on `stream` and does not synchronise.  Inputs
+ * and outputs must not overlap.  As for da_spmm, the arrays are trusted to be well formed.
+ * Errors: DA_ERR_INVALID_ARG (negative or too large sizes, null arrays with nnz > 0, workspace
+ * missing / too small / misaligned), DA_ERR_HIP (launch failure).
+ */
+int da_csr_transpose_workspace(int64_t m, int64_t k, int64_t nnz, size_t *bytes /* host, out */);
+int da_csr_transpose(int64_t m, int64_t k, int64_t nnz,
+                     const int32_t *rowptr, const int32_t *colind, const float *vals,
+                     int32_t *t_rowptr, int32_t *t_colind, float *t_vals,
+                     void *workspace, size_t workspace_bytes, void *stream);
 
 /* "RB+RM+SR" ... "EB+CM+PR" (Table 1 naming); NULL for an id outside 0..7.  Host string, static. */
 const char *da_spmm_algo_name(int algo);

@@ -22,7 +22,8 @@ DA_OK, DA_ERR_INVALID_ARG, DA_ERR_BAD_ALGO, DA_ERR_UNSUPPORTED, DA_ERR_HIP = ran
  DA_EB_RM_SR, DA_EB_RM_PR, DA_EB_CM_SR, DA_EB_CM_PR) = range(8)
 DA_NUM_ALGOS = 8
 DA_ROW_MAJOR, DA_COL_MAJOR = 0, 1
-EXPORTS = ("da_spmm", "da_spmm_ex", "da_spmm_select", "da_spmm_features", "da_spmm_algo_name", "da_spmm_last_error")
+EXPORTS = ("da_spmm", "da_spmm_ex", "da_spmm_select", "da_spmm_features", "da_csr_transpose_workspace",
+           "da_csr_transpose", "da_spmm_algo_name", "da_spmm_last_error")
 
 
 class da_features(ctypes.Structure):
@@ -41,6 +42,10 @@ _lib.da_spmm_select.argtypes = [ctypes.POINTER(da_features)]
 _lib.da_spmm_select.restype = ctypes.c_int
 _lib.da_spmm_features.argtypes = [_i64, _i64, _vp, _vp, ctypes.POINTER(da_features)]
 _lib.da_spmm_features.restype = ctypes.c_int
+_lib.da_csr_transpose_workspace.argtypes = [_i64, _i64, _i64, ctypes.POINTER(ctypes.c_size_t)]
+_lib.da_csr_transpose_workspace.restype = ctypes.c_int
+_lib.da_csr_transpose.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.da_csr_transpose.restype = ctypes.c_int
 _lib.da_spmm_algo_name.argtypes = [ctypes.c_int]
 _lib.da_spmm_algo_name.restype = ctypes.c_char_p
 _lib.da_spmm_last_error.argtypes = []
@@ -147,6 +152,31 @@ def da_spmm_features(m, N, rowptr, stream=None) -> dict:
     if st != DA_OK:
         raise DaSpmmError(st, da_spmm_last_error())
     return {n: getattr(out, n) for n, _ in da_features._fields_}
+
+
+def da_csr_transpose_workspace(m, k, nnz) -> int:
+    """Bytes of device workspace da_csr_transpose needs."""
+    out = ctypes.c_size_t(0)
+    st = int(_lib.da_csr_transpose_workspace(int(m), int(k), int(nnz), ctypes.byref(out)))
+    if st != DA_OK:
+        raise DaSpmmError(st, da_spmm_last_error())
+    return int(out.value)
+
+
+def da_csr_transpose_status(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, workspace,
+                            workspace_bytes, stream=None) -> int:
+    return int(_lib.da_csr_transpose(int(m), int(k), int(nnz), _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                     _ptr(t_rowptr), _ptr(t_colind), _ptr(t_vals), _ptr(workspace),
+                                     int(workspace_bytes), _stream(stream)))
+
+
+def da_csr_transpose(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, workspace, workspace_bytes,
+                     stream=None) -> None:
+    """CSR arrays of A^T on the device; arguments as in include/da_spmm.h."""
+    st = da_csr_transpose_status(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, workspace,
+                                 workspace_bytes, stream)
+    if st != DA_OK:
+        raise DaSpmmError(st, da_spmm_last_error())
 
 
 def da_spmm_algo_name(algo: int):

@@ -3,6 +3,7 @@
 // The C ABI is declared and documented in include/da_spmm.h.
 #include "da_spmm.h"
 #include "da_spmm_kernels.hip"
+#include "da_transpose_kernels.hip"
 
 #include <atomic>
 #include <cmath>
@@ -256,6 +257,35 @@ int dispatch(Family fam, const Geometry& g, const Problem& p) {
 const char* const kNames[DA_NUM_ALGOS] = {
     "RB+RM+SR", "RB+RM+PR", "RB+CM+SR", "RB+CM+PR", "EB+RM+SR", "EB+RM+PR", "EB+CM+SR", "EB+CM+PR"};
 
+// Workspace of da_csr_transpose: two key buffers and two payload buffers of nnz ints for the
+// ping-pong of the radix passes, the per-block digit histograms of one pass, and the chunk sums of
+// their prefix scan.  Every part starts on a 256-byte boundary.
+struct TransposePlan {
+    int passes, nblocks;
+    long hist_len, parts;
+    size_t off_keys[2], off_idx[2], off_hist, off_part, bytes;
+};
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+TransposePlan plan_transpose(int64_t k, int64_t nnz) {
+    TransposePlan t{};
+    int bits = 1;
+    while (bits < 31 && (int64_t(1) << bits) < k) ++bits;             // column indices are < 2^bits
+    t.passes = (bits + kRadixBits - 1) / kRadixBits;
+    t.nblocks = (int)((nnz + kSortTile - 1) / kSortTile);
+    t.hist_len = (long)kBins * t.nblocks;
+    t.parts = (t.hist_len + kScanChunk - 1) / kScanChunk;
+    size_t off = 0;
+    const size_t per = align256((size_t)nnz * sizeof(int));
+    for (int i = 0; i < 2; ++i) { t.off_keys[i] = off; off += per; }
+    for (int i = 0; i < 2; ++i) { t.off_idx[i] = off; off += per; }
+    t.off_hist = off; off += align256((size_t)t.hist_len * sizeof(int));
+    t.off_part = off; off += align256((size_t)t.parts * sizeof(int));
+    t.bytes = off > 0 ? off : 256;
+    return t;
+}
+
 }  // namespace
 
 extern "C" {
@@ -337,6 +367,69 @@ int da_spmm_features(int64_t m, int64_t N, const int32_t* rowptr, void* stream, 
     out->row_nnz_mean = mean;
     out->row_nnz_std = std::sqrt(var);
     out->row_nnz_max = (double)h[1];
+    return DA_OK;
+}
+
+int da_csr_transpose_workspace(int64_t m, int64_t k, int64_t nnz, size_t* bytes)
+{
+    if (!bytes) return fail(DA_ERR_INVALID_ARG, "null bytes%s");
+    if (m < 0 || k < 0 || nnz < 0) return fail(DA_ERR_INVALID_ARG, "negative size%s");
+    if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
+        return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
+    *bytes = plan_transpose(k, nnz).bytes;
+    return DA_OK;
+}
+
+int da_csr_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                     const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (m < 0 || k < 0 || nnz < 0) return fail(DA_ERR_INVALID_ARG, "negative size%s");
+    if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
+        return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
+    if (!t_rowptr) return fail(DA_ERR_INVALID_ARG, "null t_rowptr%s");
+    if (nnz > 0 && (m == 0 || k == 0)) return fail(DA_ERR_INVALID_ARG, "stored entries in a matrix without rows or columns%s");
+    if (nnz > 0 && (!rowptr || !colind || !vals || !t_colind || !t_vals))
+        return fail(DA_ERR_INVALID_ARG, "null array with nnz > 0%s");
+    const TransposePlan t = plan_transpose(k, nnz);
+    if (nnz > 0 && (!workspace || workspace_bytes < t.bytes))
+        return fail(DA_ERR_INVALID_ARG, "workspace missing or smaller than da_csr_transpose_workspace reports%s");
+    if (nnz > 0 && reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return fail(DA_ERR_INVALID_ARG, "workspace is not 256-byte aligned%s");
+    hipStream_t s = (hipStream_t)stream;
+    const int n = (int)nnz;
+    char* ws = static_cast<char*>(workspace);
+    const int* sorted_keys = nullptr;
+    if (n > 0) {
+        int* keys[2] = {reinterpret_cast<int*>(ws + t.off_keys[0]), reinterpret_cast<int*>(ws + t.off_keys[1])};
+        int* idx[2] = {reinterpret_cast<int*>(ws + t.off_idx[0]), reinterpret_cast<int*>(ws + t.off_idx[1])};
+        int* hist = reinterpret_cast<int*>(ws + t.off_hist);
+        int* part = reinterpret_cast<int*>(ws + t.off_part);
+        const int* keys_in = colind;
+        const int* idx_in = nullptr;
+        for (int p = 0; p < t.passes; ++p) {
+            const int shift = p * kRadixBits;
+            int* keys_out = keys[p & 1];
+            int* idx_out = idx[p & 1];
+            hipLaunchKernelGGL(radix_count_kernel, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, n, shift, hist, t.nblocks);
+            hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
+            hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(kSortBlock), 0, s, part, (int)t.parts);
+            hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
+            if (p == t.passes - 1)
+                hipLaunchKernelGGL(radix_scatter_kernel<true>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, idx_in, n,
+                                   shift, hist, t.nblocks, keys_out, idx_out, rowptr, (int)m, vals, t_colind, t_vals);
+            else
+                hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, idx_in, n,
+                                   shift, hist, t.nblocks, keys_out, idx_out, rowptr, (int)m, vals, t_colind, t_vals);
+            keys_in = keys_out;
+            idx_in = idx_out;
+        }
+        sorted_keys = keys_in;
+    }
+    hipLaunchKernelGGL(rowptr_from_sorted_kernel, dim3((unsigned)((k + 1 + kSortBlock - 1) / kSortBlock)), dim3(kSortBlock),
+                       0, s, sorted_keys, n, (int)k, t_rowptr);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "da_csr_transpose launch");
     return DA_OK;
 }
 

@@ -21,7 +21,7 @@ from paper_2202_08556_amd import binding as da  # noqa: E402
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "da_spmm.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(da_spmm\w*)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(da_(?:spmm|csr)\w*)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():
@@ -51,6 +51,23 @@ def test_argument_errors_without_device_work():
     assert f(4, 4, 0, None, None, None, None, None, 5, stream=0) == da.DA_OK               # N == 0: no-op
     with pytest.raises(da.DaSpmmError):
         da.da_spmm(4, 4, 4, None, None, None, None, None, 0, stream=0)
+
+
+def test_transpose_argument_errors_without_device_work():
+    assert da.da_csr_transpose_workspace(10, 10, 0) >= 0
+    big = da.da_csr_transpose_workspace(1 << 20, 1 << 20, 1 << 24)
+    assert big >= 4 * 4 * (1 << 24) and big % 256 == 0            # two key and two payload buffers at least
+    with pytest.raises(da.DaSpmmError):
+        da.da_csr_transpose_workspace(-1, 10, 5)
+    with pytest.raises(da.DaSpmmError):
+        da.da_csr_transpose_workspace(10, 10, 1 << 31)
+    f = da.da_csr_transpose_status
+    assert f(-1, 4, 4, 0, 0, 0, 0, 0, 0, 0, 0, stream=0) == da.DA_ERR_INVALID_ARG
+    assert f(4, 4, 4, 1, 1, 1, None, 1, 1, 1, 1 << 20, stream=0) == da.DA_ERR_INVALID_ARG     # null t_rowptr
+    assert f(4, 4, 4, 1, None, 1, 1, 1, 1, 1, 1 << 20, stream=0) == da.DA_ERR_INVALID_ARG     # null colind
+    assert f(0, 4, 4, 1, 1, 1, 1, 1, 1, 1, 1 << 20, stream=0) == da.DA_ERR_INVALID_ARG        # entries without rows
+    assert f(4, 4, 4, 256, 256, 256, 256, 256, 256, 256, 16, stream=0) == da.DA_ERR_INVALID_ARG   # workspace too small
+    assert "workspace" in da.da_spmm_last_error()
 
 
 def test_ex_argument_errors_without_device_work():

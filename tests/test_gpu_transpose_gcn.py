@@ -1,0 +1,174 @@
+"""da_csr_transpose against the oracle's transpose (bit for bit: index work and copied values), and
+the graph-convolution layer (aggregation A.X forward, A^T.dY backward, Sec. 6) against the fp64
+oracle within the SpMM tolerance |C - C_ref| <= 1e-5 * (|A|.|B|)_ij + 1e-6."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as orc
+from paper_2202_08556_amd import generators as gen
+
+pytestmark = pytest.mark.gpu
+
+
+def heavy_column():
+    """70001 rows with one entry each, all but a few in column 3: one digit takes whole blocks."""
+    m, k = 70001, 50
+    colind = np.full(m, 3, dtype=np.int32)
+    colind[::1000] = 49
+    colind[5] = 0
+    vals = np.arange(m, dtype=np.float32)
+    return gen.CSR(m=m, k=k, rowptr=np.arange(m + 1, dtype=np.int32), colind=colind, vals=vals, seed=0, name="heavy_column")
+
+
+def duplicates_unsorted():
+    """Rows whose columns are not sorted and repeat: stored order must survive among equal (row, column)."""
+    rng = np.random.default_rng(77)
+    m, k = 300, 40
+    lens = rng.integers(0, 30, size=m)
+    rowptr = np.zeros(m + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum(lens)
+    colind = rng.integers(0, k, size=int(rowptr[-1])).astype(np.int32)
+    vals = rng.standard_normal(int(rowptr[-1])).astype(np.float32)
+    return gen.CSR(m=m, k=k, rowptr=rowptr, colind=colind, vals=vals, seed=77, name="duplicates_unsorted")
+
+
+def transpose_cases():
+    yield gen.fig6a_csr()
+    yield gen.uniform_csr(m=37, k=53, mean_len=5, seed=31)                      # one pass (k <= 1024)
+    yield gen.uniform_csr(m=1237, k=911, mean_len=11, seed=7)
+    yield gen.lognormal_csr(3000, 12.0, 3.0, seed=35, name="lognormal")        # two passes
+    yield gen.powerlaw_csr(m=8192, seed=2001)                                   # hot columns, several blocks
+    yield gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001)
+    yield gen.stencil27_csr(12, 13, 14, seed=3001)
+    yield gen.uniform_csr(m=5000, k=1200000, mean_len=20, seed=51)              # three passes, wide and mostly empty A^T
+    yield gen.uniform_csr(m=100000, k=7, mean_len=3, seed=52)                   # tall: 7 long rows in A^T
+    yield heavy_column()
+    yield duplicates_unsorted()
+    yield gen.CSR(m=5, k=9, rowptr=np.zeros(6, dtype=np.int32), colind=np.zeros(0, np.int32),
+                  vals=np.zeros(0, np.float32), seed=0, name="no_entries")
+
+
+def device_transpose(a, sentinel=True):
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    rp, ci, va = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (a.rowptr, a.colind, a.vals))
+    nnz = int(a.colind.size)
+    t_rp = torch.full((a.k + 1,), -7, dtype=torch.int32, device=dev)
+    t_ci = torch.full((nnz,), -7, dtype=torch.int32, device=dev)
+    t_va = torch.full((nnz,), float("nan"), dtype=torch.float32, device=dev)
+    nbytes = da.da_csr_transpose_workspace(a.m, a.k, nnz)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    da.da_csr_transpose(a.m, a.k, nnz, rp, ci, va, t_rp, t_ci, t_va, ws, nbytes)
+    torch.cuda.synchronize()
+    return t_rp.cpu().numpy(), t_ci.cpu().numpy(), t_va.cpu().numpy()
+
+
+@pytest.mark.parametrize("a", list(transpose_cases()), ids=lambda a: a.name)
+def test_transpose_matches_oracle_bit_for_bit(a):
+    print(f"transpose case {a.name} m={a.m} k={a.k} nnz={a.colind.size}", flush=True)
+    ref = orc.csr_transpose(a.rowptr, a.colind, a.vals, a.k)
+    got = device_transpose(a)
+    assert np.array_equal(got[0], ref[0])
+    assert np.array_equal(got[1], ref[1])
+    assert np.array_equal(got[2].view(np.uint32), ref[2].view(np.uint32))
+
+
+def test_transpose_is_deterministic_and_its_own_inverse():
+    a = gen.powerlaw_csr(m=8192, seed=2001)
+    t1 = device_transpose(a)
+    t2 = device_transpose(a)
+    assert all(np.array_equal(x, y) for x, y in zip(t1, t2))
+    back = device_transpose(gen.CSR(m=a.k, k=a.m, rowptr=t1[0], colind=t1[1], vals=t1[2], seed=0, name="t"))
+    assert np.array_equal(back[0], a.rowptr) and np.array_equal(back[1], a.colind) and np.array_equal(back[2], a.vals)
+
+
+def test_transpose_argument_errors():
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    a = gen.uniform_csr(m=37, k=53, mean_len=5, seed=31)
+    nnz = int(a.colind.size)
+    rp, ci, va = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals))
+    t_rp = torch.zeros(a.k + 1, dtype=torch.int32, device=dev)
+    t_ci = torch.zeros(nnz, dtype=torch.int32, device=dev)
+    t_va = torch.zeros(nnz, dtype=torch.float32, device=dev)
+    nbytes = da.da_csr_transpose_workspace(a.m, a.k, nnz)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    bad = da.DA_ERR_INVALID_ARG
+    assert da.da_csr_transpose_status(a.m, a.k, nnz, rp, ci, va, t_rp, t_ci, t_va, ws, nbytes - 1) == bad
+    assert "workspace" in da.da_spmm_last_error()
+    assert da.da_csr_transpose_status(a.m, a.k, nnz, rp, ci, va, t_rp, t_ci, t_va, None, 0) == bad
+    assert da.da_csr_transpose_status(a.m, a.k, nnz, rp, ci, va, t_rp, t_ci, t_va, ws.data_ptr() + 4, nbytes) == bad
+    assert da.da_csr_transpose_status(-1, a.k, nnz, rp, ci, va, t_rp, t_ci, t_va, ws, nbytes) == bad
+    assert da.da_csr_transpose_status(a.m, a.k, nnz, rp, None, va, t_rp, t_ci, t_va, ws, nbytes) == bad
+    assert da.da_csr_transpose_status(a.m, a.k, 1 << 31, rp, ci, va, t_rp, t_ci, t_va, ws, nbytes) == bad
+    assert da.da_csr_transpose_status(a.m, a.k, nnz, rp, ci, va, t_rp, t_ci, t_va, ws, nbytes) == da.DA_OK
+    torch.cuda.synchronize()
+
+
+GRAPHS = [("powerlaw", lambda: gen.powerlaw_csr(m=4096, seed=2101), [16, 64]),
+          ("rect_lognormal", lambda: gen.lognormal_csr(3000, 12.0, 3.0, seed=35, name="ln"), [32]),
+          ("rect_uniform", lambda: gen.uniform_csr(m=1237, k=911, mean_len=11, seed=7), [20, 256])]
+
+
+@pytest.mark.parametrize("name,make,Ns", GRAPHS, ids=[g[0] for g in GRAPHS])
+def test_aggregate_forward_and_backward_match_oracle(name, make, Ns):
+    from paper_2202_08556_amd import gcn
+    a = make()
+    graph = gcn.SparseGraph.from_numpy(a)
+    for N in Ns:
+        print(f"aggregate case {name} N={N}", flush=True)
+        X = gen.dense(a.k, N, "normal", seed=a.seed + N)
+        G = gen.dense(a.m, N, "uniform", seed=a.seed + N + 1)
+        Xd = torch.from_numpy(X).cuda().requires_grad_(True)
+        Y = gcn.aggregate(graph, Xd)
+        Y.backward(torch.from_numpy(G).cuda())
+        torch.cuda.synchronize()
+        c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, X)
+        assert orc.tolerance_ratio(Y.detach().cpu().numpy(), c_ref, s_abs) <= 1.0
+        d_ref, sd_abs = orc.spmm_transposed(a.rowptr, a.colind, a.vals, G, a.k)
+        assert orc.tolerance_ratio(Xd.grad.cpu().numpy(), d_ref, sd_abs) <= 1.0
+
+
+def test_backward_exact_on_integer_inputs():
+    from paper_2202_08556_amd import gcn
+    a = gen.integer_twin(gen.powerlaw_csr(m=4096, seed=2102))
+    N = 32
+    G = gen.dense_int(a.m, N, seed=9)
+    graph = gcn.SparseGraph.from_numpy(a)
+    Xd = torch.zeros((a.k, N), device="cuda:0", requires_grad=True)
+    gcn.aggregate(graph, Xd).backward(torch.from_numpy(G).cuda())
+    torch.cuda.synchronize()
+    d_ref, _ = orc.spmm_transposed(a.rowptr, a.colind, a.vals, G, a.k)
+    assert orc.bit_mismatches(Xd.grad.cpu().numpy(), d_ref) == 0
+
+
+def test_graph_conv_layer_matches_fp64_layer():
+    """Whole layer relu(A.(X.W)+b), forward and all three gradients.  The dense products run in the
+    fp32 GEMM library, so the bound is a relative one on the size of each result."""
+    from paper_2202_08556_amd import gcn
+    a = gen.powerlaw_csr(m=2048, seed=2103)
+    fin, fout = 48, 32
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((a.m, fin)).astype(np.float32)
+    d_out = rng.standard_normal((a.m, fout)).astype(np.float32)
+    torch.manual_seed(3)
+    layer = gcn.GraphConv(fin, fout).cuda()
+    with torch.no_grad():
+        layer.bias.uniform_(-0.1, 0.1)
+    W = layer.weight.detach().cpu().numpy()
+    b = layer.bias.detach().cpu().numpy()
+    ref_out, Z = orc.gcn_layer(a.rowptr, a.colind, a.vals, X, W, b)
+    # a unit whose pre-activation is within rounding of zero may fall on either side of the relu in
+    # fp32: give those units no incoming gradient, so that the comparison does not hinge on them
+    d_out[np.abs(Z) <= 1e-4] = 0.0
+    dX, dW, db = orc.gcn_layer_backward(a.rowptr, a.colind, a.vals, X, W, Z, d_out)
+    graph = gcn.SparseGraph.from_numpy(a)
+    Xd = torch.from_numpy(X).cuda().requires_grad_(True)
+    out = layer(graph, Xd)
+    out.backward(torch.from_numpy(d_out).cuda())
+    torch.cuda.synchronize()
+    got = out.detach().cpu().numpy()
+    assert np.max(np.abs(got - ref_out)) <= 2e-5 * np.max(np.abs(ref_out)) + 1e-6
+    for g, r in ((Xd.grad, dX), (layer.weight.grad, dW), (layer.bias.grad, db)):
+        assert np.max(np.abs(g.cpu().numpy() - r)) <= 5e-5 * np.max(np.abs(r)) + 1e-6
