@@ -75,3 +75,16 @@ def test_skewed_full_integer_bit_exact():
 def test_sweep_members(j, N):
     a = gen.sweep_csr(j)
     check_all(a, gen.dense(a.k, N, "uniform", seed=a.seed), f"sweep{j} N={N}")
+
+
+@pytest.mark.parametrize("which", ["powerlaw", "skewed"])
+def test_transpose_full(which):
+    """da_csr_transpose at the benchmark sizes (13 M / 33 M entries, thousands of sort blocks,
+    columns hit a million times): bit for bit against the oracle's stable re-ordering."""
+    from tests.test_gpu_transpose_gcn import device_transpose
+    a = gen.powerlaw_csr(seed=gen.config_seed(2)) if which == "powerlaw" else gen.skewed_csr(seed=gen.config_seed(4))
+    print(f"transpose full {which} nnz={a.nnz}", flush=True)
+    ref = orc.csr_transpose(a.rowptr, a.colind, a.vals, a.k)
+    got = device_transpose(a)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    assert np.array_equal(got[2].view(np.uint32), ref[2].view(np.uint32))
