@@ -131,6 +131,20 @@ int da_spmm_select(const da_features *f);
 int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, da_features *out);
 
 /*
+ * Debug aid: check on the device that the CSR arrays are well formed -- rowptr[0] == 0, rowptr
+ * non-decreasing, rowptr[m] == nnz (skipped when nnz is passed as -1), every colind in [0, k).
+ * The product kernels trust these properties (Sec. 3.1 takes a valid CSR matrix as given) and a
+ * violation can make them read out of bounds, so this call is the way to vet arrays of unknown
+ * origin.  colind is only read after the row pointers passed, over rowptr[m] entries.
+ * Allocates an 8-byte device buffer, synchronises `stream`, frees the buffer.  Returns DA_OK,
+ * DA_ERR_INVALID_ARG (last error names the violated property) or DA_ERR_HIP.
+ * Setting the environment variable DA_SPMM_DEBUG_VALIDATE=1 makes da_spmm, da_spmm_ex and
+ * da_csr_transpose run this check first on every call (and return its error).
+ */
+int da_csr_validate(int64_t m, int64_t k, int64_t nnz, const int32_t *rowptr, const int32_t *colind,
+                    void *stream);
+
+/*
  * CSR arrays of the transpose.  The paper's GCN experiment (Sec. 6) runs the SpMM inside a graph
  * neural network layer; training such a layer needs the gradient of <G, A*X> with respect to X,
  * which is A^T * G -- the same sparse-times-dense product on the transposed matrix.  This call

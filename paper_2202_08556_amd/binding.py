@@ -23,7 +23,7 @@ DA_OK, DA_ERR_INVALID_ARG, DA_ERR_BAD_ALGO, DA_ERR_UNSUPPORTED, DA_ERR_HIP = ran
 DA_NUM_ALGOS = 8
 DA_ROW_MAJOR, DA_COL_MAJOR = 0, 1
 EXPORTS = ("da_spmm", "da_spmm_ex", "da_spmm_select", "da_spmm_features", "da_csr_transpose_workspace",
-           "da_csr_transpose", "da_spmm_algo_name", "da_spmm_last_error")
+           "da_csr_transpose", "da_csr_validate", "da_spmm_algo_name", "da_spmm_last_error")
 
 
 class da_features(ctypes.Structure):
@@ -46,6 +46,8 @@ _lib.da_csr_transpose_workspace.argtypes = [_i64, _i64, _i64, ctypes.POINTER(cty
 _lib.da_csr_transpose_workspace.restype = ctypes.c_int
 _lib.da_csr_transpose.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.da_csr_transpose.restype = ctypes.c_int
+_lib.da_csr_validate.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp]
+_lib.da_csr_validate.restype = ctypes.c_int
 _lib.da_spmm_algo_name.argtypes = [ctypes.c_int]
 _lib.da_spmm_algo_name.restype = ctypes.c_char_p
 _lib.da_spmm_last_error.argtypes = []
@@ -175,6 +177,17 @@ def da_csr_transpose(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals
     """CSR arrays of A^T on the device; arguments as in include/da_spmm.h."""
     st = da_csr_transpose_status(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, workspace,
                                  workspace_bytes, stream)
+    if st != DA_OK:
+        raise DaSpmmError(st, da_spmm_last_error())
+
+
+def da_csr_validate_status(m, k, nnz, rowptr, colind, stream=None) -> int:
+    return int(_lib.da_csr_validate(int(m), int(k), int(nnz), _ptr(rowptr), _ptr(colind), _stream(stream)))
+
+
+def da_csr_validate(m, k, nnz, rowptr, colind, stream=None) -> None:
+    """Raise DaSpmmError unless the CSR arrays are well formed (nnz = -1: do not compare rowptr[m])."""
+    st = da_csr_validate_status(m, k, nnz, rowptr, colind, stream)
     if st != DA_OK:
         raise DaSpmmError(st, da_spmm_last_error())
 

@@ -286,9 +286,59 @@ TransposePlan plan_transpose(int64_t k, int64_t nnz) {
     return t;
 }
 
+// DA_SPMM_DEBUG_VALIDATE=1 makes da_spmm / da_spmm_ex / da_csr_transpose check the CSR arrays on
+// the device before they launch anything (this synchronises the stream)
+bool debug_validate() {
+    const char* v = std::getenv("DA_SPMM_DEBUG_VALIDATE");
+    return v && *v && std::strcmp(v, "0") != 0;
+}
+
 }  // namespace
 
 extern "C" {
+
+int da_csr_validate(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, void* stream)
+{
+    if (m < 0 || k < 0 || nnz < -1) return fail(DA_ERR_INVALID_ARG, "negative size%s");
+    if (m > 0x7ffffffeLL || k > 0x7fffffffLL || nnz > 0x7fffffffLL)
+        return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
+    if (m == 0) return nnz > 0 ? fail(DA_ERR_INVALID_ARG, "stored entries in a matrix without rows%s") : DA_OK;
+    if (!rowptr) return fail(DA_ERR_INVALID_ARG, "null rowptr%s");
+    hipStream_t st = (hipStream_t)stream;
+    unsigned* dflags = nullptr;
+    hipError_t e = hipMalloc(&dflags, 2 * sizeof(unsigned));
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc");
+    unsigned h[2] = {0, 0};
+    const long cap = (long)cu_count() * 8;
+    auto blocks_for = [&](long n) { long b = (n + kBlock - 1) / kBlock; return (unsigned)(b > cap ? cap : (b < 1 ? 1 : b)); };
+    e = hipMemsetAsync(dflags, 0, sizeof h, st);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(validate_rowptr_kernel, dim3(blocks_for(m)), dim3(kBlock), 0, st, (int)m, rowptr, dflags);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(h, dflags, sizeof h, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    int status = DA_OK;
+    if (e == hipSuccess) {
+        const int64_t dev_nnz = (int64_t)(int32_t)h[1];
+        if (h[0] & kBadFirst) status = fail(DA_ERR_INVALID_ARG, "malformed CSR: rowptr[0] != 0%s");
+        else if (h[0] & kBadOrder) status = fail(DA_ERR_INVALID_ARG, "malformed CSR: rowptr decreases%s");
+        else if (nnz >= 0 && dev_nnz != nnz) status = fail(DA_ERR_INVALID_ARG, "malformed CSR: rowptr[m] differs from nnz%s");
+        else if (dev_nnz > 0 && !colind) status = fail(DA_ERR_INVALID_ARG, "null colind with stored entries%s");
+        else if (dev_nnz > 0) {
+            hipLaunchKernelGGL(validate_colind_kernel, dim3(blocks_for(dev_nnz)), dim3(kBlock), 0, st, (int)dev_nnz, (int)k,
+                               colind, dflags);
+            e = hipGetLastError();
+            if (e == hipSuccess) e = hipMemcpyAsync(h, dflags, sizeof h, hipMemcpyDeviceToHost, st);
+            if (e == hipSuccess) e = hipStreamSynchronize(st);
+            if (e == hipSuccess && (h[0] & kBadColumn))
+                status = fail(DA_ERR_INVALID_ARG, "malformed CSR: column index outside [0, k)%s");
+        }
+    }
+    (void)hipFree(dflags);
+    if (e != hipSuccess) return hip_fail(e, "da_csr_validate");
+    return status;
+}
 
 int da_spmm_ex(int64_t m, int64_t k, int64_t N, const int32_t* rowptr, const int32_t* colind,
                const float* vals, const float* B, int64_t ldb, int layout_b, float* C, int64_t ldc,
@@ -306,6 +356,10 @@ int da_spmm_ex(int64_t m, int64_t k, int64_t N, const int32_t* rowptr, const int
     if (!rowptr || !C) return fail(DA_ERR_INVALID_ARG, "null rowptr or C%s");
     // colind, vals and B are read only through stored entries; they may be null when nnz == 0,
     // which only the device knows
+    if (debug_validate()) {
+        const int v = da_csr_validate(m, k, -1, rowptr, colind, stream);
+        if (v != DA_OK) return v;
+    }
 
     Strides sd;
     sd.rb = layout_b == DA_ROW_MAJOR ? ldb : 1;
@@ -391,6 +445,10 @@ int da_csr_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, c
     if (nnz > 0 && (m == 0 || k == 0)) return fail(DA_ERR_INVALID_ARG, "stored entries in a matrix without rows or columns%s");
     if (nnz > 0 && (!rowptr || !colind || !vals || !t_colind || !t_vals))
         return fail(DA_ERR_INVALID_ARG, "null array with nnz > 0%s");
+    if (debug_validate() && m > 0) {
+        const int v = da_csr_validate(m, k, nnz, rowptr, colind, stream);
+        if (v != DA_OK) return v;
+    }
     const TransposePlan t = plan_transpose(k, nnz);
     if (nnz > 0 && (!workspace || workspace_bytes < t.bytes))
         return fail(DA_ERR_INVALID_ARG, "workspace missing or smaller than da_csr_transpose_workspace reports%s");

@@ -763,4 +763,35 @@ __global__ __launch_bounds__(kBlock) void features_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Well-formedness checks of the CSR arrays (debug aid).  flags[0] collects violation bits,
+// flags[1] receives rowptr[m].  The column check must only run after the row-pointer check
+// passed: it trusts rowptr[m] as the number of stored entries.
+// ------------------------------------------------------------------------------------------
+enum : unsigned { kBadFirst = 1u, kBadOrder = 2u, kBadColumn = 4u };
+
+__global__ __launch_bounds__(kBlock) void validate_rowptr_kernel(int m, const int* __restrict__ rowptr,
+                                                                 unsigned* __restrict__ flags)
+{
+    unsigned bad = 0;
+    for (long i = (long)blockIdx.x * kBlock + threadIdx.x; i < m; i += (long)gridDim.x * kBlock)
+        if (rowptr[i + 1] < rowptr[i]) bad |= kBadOrder;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (rowptr[0] != 0) bad |= kBadFirst;
+        flags[1] = (unsigned)rowptr[m];
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
+__global__ __launch_bounds__(kBlock) void validate_colind_kernel(int nnz, int k, const int* __restrict__ colind,
+                                                                 unsigned* __restrict__ flags)
+{
+    unsigned bad = 0;
+    for (long p = (long)blockIdx.x * kBlock + threadIdx.x; p < nnz; p += (long)gridDim.x * kBlock) {
+        const int c = colind[p];
+        if (c < 0 || c >= k) bad |= kBadColumn;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
 }  // namespace daspmm

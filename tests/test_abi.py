@@ -70,6 +70,18 @@ def test_transpose_argument_errors_without_device_work():
     assert "workspace" in da.da_spmm_last_error()
 
 
+def test_validate_argument_errors_without_device_work():
+    f = da.da_csr_validate_status
+    assert f(-1, 4, 0, 0, 0, stream=0) == da.DA_ERR_INVALID_ARG
+    assert f(4, 4, -2, 0, 0, stream=0) == da.DA_ERR_INVALID_ARG
+    assert f(2 ** 31, 4, 0, 0, 0, stream=0) == da.DA_ERR_INVALID_ARG
+    assert f(0, 4, 0, None, None, stream=0) == da.DA_OK
+    assert f(0, 4, 3, None, None, stream=0) == da.DA_ERR_INVALID_ARG
+    assert f(4, 4, 3, None, None, stream=0) == da.DA_ERR_INVALID_ARG          # null rowptr
+    with pytest.raises(da.DaSpmmError):
+        da.da_csr_validate(4, 4, 3, None, None, stream=0)
+
+
 def test_ex_argument_errors_without_device_work():
     f = da.da_spmm_ex_status
     R, Cm = da.DA_ROW_MAJOR, da.DA_COL_MAJOR

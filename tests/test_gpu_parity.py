@@ -266,3 +266,53 @@ def test_storage_orders_and_leading_dimensions(gpu, b_col, c_col):
             idx = np.arange(c_host.size).reshape(-1)
             orc.dense_view(mask, a.m, N, ldc, c_col)[...] = False
             assert np.all(c_host[mask] == -5.0), "padding of C was written"
+
+
+def test_validate_catches_malformed_csr_and_debug_switch_guards_the_product(monkeypatch):
+    """da_csr_validate names each kind of violation; with DA_SPMM_DEBUG_VALIDATE=1 the product and
+    the transpose refuse malformed arrays before any of their kernels is launched."""
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    a = gen.uniform_csr(m=300, k=200, mean_len=6, seed=61)
+    nnz = int(a.colind.size)
+    up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    rp, ci, va = up(a.rowptr), up(a.colind), up(a.vals)
+    da.da_csr_validate(a.m, a.k, nnz, rp, ci)
+    da.da_csr_validate(a.m, a.k, -1, rp, ci)
+    bad = da.DA_ERR_INVALID_ARG
+
+    def status_and_text(*args):
+        st = da.da_csr_validate_status(*args)
+        return st, da.da_spmm_last_error()
+
+    assert status_and_text(a.m, a.k, nnz + 1, rp, ci) == (bad, "malformed CSR: rowptr[m] differs from nnz")
+    shifted = a.rowptr.copy(); shifted[0] = 1
+    assert status_and_text(a.m, a.k, nnz, up(shifted), ci)[1] == "malformed CSR: rowptr[0] != 0"
+    swapped = a.rowptr.copy(); swapped[[100, 101]] = swapped[[101, 100]]
+    assert swapped[100] > swapped[101]
+    assert status_and_text(a.m, a.k, nnz, up(swapped), ci)[1] == "malformed CSR: rowptr decreases"
+    for wrong in (a.k, -1, 2 ** 31 - 1):
+        c2 = a.colind.copy(); c2[nnz // 2] = wrong
+        assert status_and_text(a.m, a.k, nnz, rp, up(c2)) == (bad, "malformed CSR: column index outside [0, k)")
+    assert status_and_text(a.m, a.k - 1, nnz, rp, ci)[0] == (bad if a.colind.max() == a.k - 1 else da.DA_OK)
+
+    # the switch: same malformed arrays through the product and the transpose
+    monkeypatch.setenv("DA_SPMM_DEBUG_VALIDATE", "1")
+    N = 8
+    B = torch.zeros((a.k, N), device=dev)
+    C = torch.zeros((a.m, N), device=dev)
+    c2 = a.colind.copy(); c2[3] = a.k + 5
+    assert da.da_spmm_status(a.m, a.k, N, rp, up(c2), va, B, C, da.DA_EB_RM_SR) == bad
+    assert da.da_spmm_status(a.m, a.k, N, up(swapped), ci, va, B, C, da.DA_RB_RM_SR) == bad
+    t = (torch.zeros(a.k + 1, dtype=torch.int32, device=dev), torch.zeros(nnz, dtype=torch.int32, device=dev),
+         torch.zeros(nnz, dtype=torch.float32, device=dev))
+    nbytes = da.da_csr_transpose_workspace(a.m, a.k, nnz)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    assert da.da_csr_transpose_status(a.m, a.k, nnz, rp, up(c2), va, *t, ws, nbytes) == bad
+    # well-formed arrays still run, and give the right answer, with the switch on
+    Bn = gen.dense(a.k, N, "uniform", seed=5)
+    C = torch.full((a.m, N), float("nan"), device=dev)
+    assert da.da_spmm_status(a.m, a.k, N, rp, ci, va, up(Bn), C, da.DA_EB_RM_PR) == da.DA_OK
+    torch.cuda.synchronize()
+    c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, Bn)
+    assert orc.tolerance_ratio(C.cpu().numpy(), c_ref, s_abs) <= 1.0
