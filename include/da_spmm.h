@@ -156,7 +156,7 @@ int da_csr_validate(int64_t m, int64_t k, int64_t nnz, const int32_t *rowptr, co
  *            the call; inside every row of A^T the indices ascend (entries of equal (row, column)
  *            keep their stored order), so the result is deterministic bit for bit
  *   workspace  device scratch of at least the size da_csr_transpose_workspace reports for the
- *            same (m, k, nnz), 256-byte aligned, owned by the caller, free for reuse once the
+ *            same (m, k, nnz) (about 24 bytes per stored entry), 256-byte aligned, owned by the caller, free for reuse once the
  *            stream has passed the call; may be NULL when nnz == 0
  * The call allocates nothing, only enqueues kernels on `stream` and does not synchronise.  Inputs
  * and outputs must not overlap.  As for da_spmm, the arrays are trusted to be well formed.

@@ -257,13 +257,13 @@ int dispatch(Family fam, const Geometry& g, const Problem& p) {
 const char* const kNames[DA_NUM_ALGOS] = {
     "RB+RM+SR", "RB+RM+PR", "RB+CM+SR", "RB+CM+PR", "EB+RM+SR", "EB+RM+PR", "EB+CM+SR", "EB+CM+PR"};
 
-// Workspace of da_csr_transpose: two key buffers and two payload buffers of nnz ints for the
-// ping-pong of the radix passes, the per-block digit histograms of one pass, and the chunk sums of
-// their prefix scan.  Every part starts on a 256-byte boundary.
+// Workspace of da_csr_transpose: two buffers each of keys, row numbers and values (nnz elements)
+// for the ping-pong of the radix passes, the per-block digit histograms of one pass, and the chunk
+// sums of their prefix scan.  Every part starts on a 256-byte boundary.
 struct TransposePlan {
-    int passes, nblocks;
+    int passes, digit_bits, nblocks;
     long hist_len, parts;
-    size_t off_keys[2], off_idx[2], off_hist, off_part, bytes;
+    size_t off_keys[2], off_rows[2], off_vals[2], off_hist, off_part, bytes;
 };
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -273,13 +273,15 @@ TransposePlan plan_transpose(int64_t k, int64_t nnz) {
     int bits = 1;
     while (bits < 31 && (int64_t(1) << bits) < k) ++bits;             // column indices are < 2^bits
     t.passes = (bits + kRadixBits - 1) / kRadixBits;
+    t.digit_bits = (bits + t.passes - 1) / t.passes;                  // equal digits, at most kRadixBits wide
     t.nblocks = (int)((nnz + kSortTile - 1) / kSortTile);
     t.hist_len = (long)kBins * t.nblocks;
     t.parts = (t.hist_len + kScanChunk - 1) / kScanChunk;
     size_t off = 0;
-    const size_t per = align256((size_t)nnz * sizeof(int));
+    const size_t per = align256((size_t)nnz * 4);
     for (int i = 0; i < 2; ++i) { t.off_keys[i] = off; off += per; }
-    for (int i = 0; i < 2; ++i) { t.off_idx[i] = off; off += per; }
+    for (int i = 0; i < 2; ++i) { t.off_rows[i] = off; off += per; }
+    for (int i = 0; i < 2; ++i) { t.off_vals[i] = off; off += per; }
     t.off_hist = off; off += align256((size_t)t.hist_len * sizeof(int));
     t.off_part = off; off += align256((size_t)t.parts * sizeof(int));
     t.bytes = off > 0 ? off : 256;
@@ -460,27 +462,34 @@ int da_csr_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, c
     const int* sorted_keys = nullptr;
     if (n > 0) {
         int* keys[2] = {reinterpret_cast<int*>(ws + t.off_keys[0]), reinterpret_cast<int*>(ws + t.off_keys[1])};
-        int* idx[2] = {reinterpret_cast<int*>(ws + t.off_idx[0]), reinterpret_cast<int*>(ws + t.off_idx[1])};
+        int* rows[2] = {reinterpret_cast<int*>(ws + t.off_rows[0]), reinterpret_cast<int*>(ws + t.off_rows[1])};
+        float* vbuf[2] = {reinterpret_cast<float*>(ws + t.off_vals[0]), reinterpret_cast<float*>(ws + t.off_vals[1])};
         int* hist = reinterpret_cast<int*>(ws + t.off_hist);
         int* part = reinterpret_cast<int*>(ws + t.off_part);
+        const int mask = (1 << t.digit_bits) - 1;
         const int* keys_in = colind;
-        const int* idx_in = nullptr;
+        const int* rows_in = nullptr;
+        const float* vals_in = vals;
         for (int p = 0; p < t.passes; ++p) {
-            const int shift = p * kRadixBits;
+            const int shift = p * t.digit_bits;
+            const bool last = p == t.passes - 1;
             int* keys_out = keys[p & 1];
-            int* idx_out = idx[p & 1];
-            hipLaunchKernelGGL(radix_count_kernel, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, n, shift, hist, t.nblocks);
+            int* rows_out = last ? t_colind : rows[p & 1];
+            float* vals_out = last ? t_vals : vbuf[p & 1];
+            hipLaunchKernelGGL(radix_count_kernel, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, n, shift, mask, hist,
+                               t.nblocks);
             hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
             hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(kSortBlock), 0, s, part, (int)t.parts);
             hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
-            if (p == t.passes - 1)
-                hipLaunchKernelGGL(radix_scatter_kernel<true>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, idx_in, n,
-                                   shift, hist, t.nblocks, keys_out, idx_out, rowptr, (int)m, vals, t_colind, t_vals);
+            if (p == 0)
+                hipLaunchKernelGGL(radix_scatter_kernel<true>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, rows_in,
+                                   vals_in, n, shift, mask, hist, t.nblocks, keys_out, rows_out, vals_out, rowptr, (int)m);
             else
-                hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, idx_in, n,
-                                   shift, hist, t.nblocks, keys_out, idx_out, rowptr, (int)m, vals, t_colind, t_vals);
+                hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys_in, rows_in,
+                                   vals_in, n, shift, mask, hist, t.nblocks, keys_out, rows_out, vals_out, rowptr, (int)m);
             keys_in = keys_out;
-            idx_in = idx_out;
+            rows_in = rows_out;
+            vals_in = vals_out;
         }
         sorted_keys = keys_in;
     }

@@ -3,9 +3,9 @@
 // <G, A.X> with respect to X is A^T.G and is computed by the same SpMM kernels on A^T.
 //
 // Row j of A^T lists the stored entries of column j of A with ascending row numbers.  CSR stores
-// entries row after row, so a STABLE sort of the entry numbers by column index is exactly that
-// order, and it is deterministic (no atomic cursors).  The sort is a least-significant-digit radix
-// sort with 10-bit digits; one pass is
+// entries row after row, so a STABLE sort of the entries by column index is exactly that order,
+// and it is deterministic (no atomic cursors on global memory).  The sort is a least-significant-
+// digit radix sort of (column, row, value) triples with digits of at most 8 bits; one pass is
 //     radix_count_kernel    per-block digit histogram                       -> hist[digit][block]
 //     scan_*_kernel         exclusive prefix sum over hist in that order    (three small kernels)
 //     radix_scatter_kernel  stable scatter: position = scanned hist entry + number of earlier
@@ -13,27 +13,31 @@
 // Inside a block each wave owns a contiguous run of entries and walks it 64 entries at a time; the
 // lanes that hold the same digit find each other with one ballot per digit bit, so the rank of an
 // entry among its peers is a population count and only one lane per distinct digit touches the
-// wave's running counter in LDS.
-// The last pass writes the transposed arrays directly (the row number of an entry comes from a
-// binary search in rowptr, its value from vals) together with the sorted keys, from which the new
-// row pointers follow by one lower-bound search per row.
+// wave's running counter in LDS.  The block first orders its tile by digit in LDS and then copies
+// it out, so that entries with the same digit leave as contiguous runs (coalesced stores) rather
+// than as single 4-byte stores.
+// The first pass reads colind / vals and derives the row number of every entry from rowptr; the
+// last pass writes straight into the arrays of A^T (row numbers become its column indices) plus
+// the sorted keys, from which the new row pointers follow by one lower-bound search per row.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace daspmm {
 
-constexpr int kRadixBits = 10;
+constexpr int kRadixBits = 8;                            // widest digit
 constexpr int kBins = 1 << kRadixBits;
-constexpr int kSortBlock = 256;
+constexpr int kSortBlock = 256;                          // one thread per bin in the bookkeeping steps
 constexpr int kSortWaves = kSortBlock / 64;
-constexpr int kSortRounds = 32;                          // 64-entry rounds per wave and block
+constexpr int kSortRounds = 16;                          // 64-entry rounds per wave and block
 constexpr int kSortWaveRun = kSortRounds * 64;           // consecutive entries owned by one wave
 constexpr int kSortTile = kSortWaves * kSortWaveRun;     // entries per block
 constexpr int kScanPerThread = 16;
 constexpr int kScanChunk = kSortBlock * kScanPerThread;  // ints per block in the scan kernels
 
-__device__ __forceinline__ int digit_of(int key, int shift) { return (key >> shift) & (kBins - 1); }
+static_assert(kBins == kSortBlock, "bookkeeping maps one thread to one bin");
+
+__device__ __forceinline__ int digit_of(int key, int shift, int mask) { return (key >> shift) & mask; }
 
 // Lanes of the wave that are valid and hold the same digit as the caller (meaningless for a lane
 // that is not valid).  Every lane of the wave must call it.
@@ -130,31 +134,9 @@ __global__ __launch_bounds__(kSortBlock) void scan_apply_kernel(int* __restrict_
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// one radix pass
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSortBlock) void radix_count_kernel(const int* __restrict__ keys, int n, int shift,
-                                                                 int* __restrict__ hist, int nblocks)
-{
-    __shared__ int cnt[kBins];
-    for (int d = threadIdx.x; d < kBins; d += kSortBlock) cnt[d] = 0;
-    __syncthreads();
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long wbase = (long)blockIdx.x * kSortTile + (long)wave * kSortWaveRun;
-    for (int r = 0; r < kSortRounds; ++r) {
-        const long e = wbase + r * 64 + lane;
-        const bool valid = e < n;
-        const int d = valid ? digit_of(keys[e], shift) : 0;
-        const unsigned long long peers = digit_peers(d, valid);
-        if (valid && lane == __ffsll((long long)peers) - 1) atomicAdd(&cnt[d], __popcll(peers));
-    }
-    __syncthreads();
-    for (int d = threadIdx.x; d < kBins; d += kSortBlock) hist[(long)d * nblocks + blockIdx.x] = cnt[d];
-}
-
-// Smallest r in [0, m-1] with rowptr[r+1] > e: the row that owns stored entry e.
-__device__ __forceinline__ int owner_row(const int* __restrict__ rowptr, int m, int e) {
-    int lo = 0, hi = m - 1;
+// Smallest r in [lo, hi] with rowptr[r+1] > e: the row that owns stored entry e, given that it
+// lies in [lo, hi].
+__device__ __forceinline__ int owner_row(const int* __restrict__ rowptr, int lo, int hi, int e) {
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
         if (rowptr[mid + 1] > e) hi = mid; else lo = mid + 1;
@@ -162,63 +144,144 @@ __device__ __forceinline__ int owner_row(const int* __restrict__ rowptr, int m, 
     return lo;
 }
 
-// hist holds the exclusive prefix sums of the pass's histograms.  idx_in == nullptr means that the
-// payload of entry e is e itself (first pass).  FINAL: besides the sorted keys, write the row
-// number and value of every entry at its sorted position instead of the payload.
-template <bool FINAL>
-__global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
-    const int* __restrict__ keys_in, const int* __restrict__ idx_in, int n, int shift,
-    const int* __restrict__ hist, int nblocks, int* __restrict__ keys_out, int* __restrict__ idx_out,
-    const int* __restrict__ rowptr, int m, const float* __restrict__ vals,
-    int* __restrict__ t_colind, float* __restrict__ t_vals)
+// ------------------------------------------------------------------------------------------
+// one radix pass; digit = (key >> shift) & mask with mask < kBins
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSortBlock) void radix_count_kernel(const int* __restrict__ keys, int n, int shift, int mask,
+                                                                 int* __restrict__ hist, int nblocks)
 {
-    __shared__ int wcnt[kSortWaves][kBins];
-    for (int d = threadIdx.x; d < kSortWaves * kBins; d += kSortBlock) (&wcnt[0][0])[d] = 0;
+    __shared__ int cnt[kBins];
+    cnt[threadIdx.x] = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long wbase = (long)blockIdx.x * kSortTile + (long)wave * kSortWaveRun;
-    // digits per wave
-    for (int r = 0; r < kSortRounds; ++r) {
-        const long e = wbase + r * 64 + lane;
-        const bool valid = e < n;
-        const int d = valid ? digit_of(keys_in[e], shift) : 0;
-        const unsigned long long peers = digit_peers(d, valid);
-        if (valid && lane == __ffsll((long long)peers) - 1) atomicAdd(&wcnt[wave][d], __popcll(peers));
-    }
-    __syncthreads();
-    // counts -> first output position of every (wave, digit)
-    for (int d = threadIdx.x; d < kBins; d += kSortBlock) {
-        int b = hist[(long)d * nblocks + blockIdx.x];
+    int key[kSortRounds];
 #pragma unroll
-        for (int w = 0; w < kSortWaves; ++w) {
-            const int c = wcnt[w][d];
-            wcnt[w][d] = b;
-            b += c;
-        }
+    for (int r = 0; r < kSortRounds; ++r) {               // all loads of the lane in flight together;
+        const long e = wbase + r * 64 + lane;             // clamped, so that they need no branch
+        key[r] = keys[e < n ? e : n - 1];
+    }
+#pragma unroll
+    for (int r = 0; r < kSortRounds; ++r) {
+        const bool valid = wbase + r * 64 + lane < n;
+        const int d = digit_of(key[r], shift, mask);
+        const unsigned long long peers = digit_peers(d, valid);
+        if (valid && lane == __ffsll((long long)peers) - 1) atomicAdd(&cnt[d], __popcll(peers));
+        __builtin_amdgcn_sched_barrier(0);                // keep the ballots of one round together
     }
     __syncthreads();
-    // stable scatter: rounds in order, peers ranked by lane number
+    hist[(long)threadIdx.x * nblocks + blockIdx.x] = cnt[threadIdx.x];
+}
+
+// hist holds the exclusive prefix sums of the pass's histograms.  FIRST: the input is the matrix
+// itself (keys_in = colind, vals_in = vals) and the row number of an entry is derived from rowptr;
+// otherwise rows_in carries it.  The outputs of the last pass are the arrays of A^T.
+template <bool FIRST>
+__global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
+    const int* __restrict__ keys_in, const int* __restrict__ rows_in, const float* __restrict__ vals_in, int n,
+    int shift, int mask, const int* __restrict__ hist, int nblocks,
+    int* __restrict__ keys_out, int* __restrict__ rows_out, float* __restrict__ vals_out,
+    const int* __restrict__ rowptr, int m)
+{
+    __shared__ int wcnt[kSortWaves][kBins];              // per wave and digit: count, then next slot in the tile
+    __shared__ int gbase[kBins];                          // global position minus tile slot, per digit
+    __shared__ int sh[kSortWaves];
+    __shared__ int skey[kSortTile];
+    __shared__ int srow[kSortTile];
+    __shared__ float sval[kSortTile];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int w = 0; w < kSortWaves; ++w) wcnt[w][threadIdx.x] = 0;
+    const long tbase = (long)blockIdx.x * kSortTile;
+    const long wbase = tbase + (long)wave * kSortWaveRun;
+    const int tile_count = (int)min((long)kSortTile, (long)n - tbase);
+    // the lane's 16 entries: every load is issued before the first one is used (indices clamped to
+    // the last entry instead of branching; `valid` masks the surplus lanes of the last block)
+    int key[kSortRounds], row[kSortRounds];
+    float val[kSortRounds];
+#pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const long e = wbase + r * 64 + lane;
-        const bool valid = e < n;
-        const int key = valid ? keys_in[e] : 0;
-        const int d = digit_of(key, shift);
-        const unsigned long long peers = digit_peers(d, valid);
-        const int leader = __ffsll((long long)peers) - 1;
-        int first = 0;
-        if (valid && lane == leader) first = atomicAdd(&wcnt[wave][d], __popcll(peers));
-        first = __shfl(first, leader & 63);
-        if (valid) {
-            const int pos = first + __popcll(peers & ((1ull << lane) - 1ull));
-            const int idx = idx_in ? idx_in[e] : (int)e;
-            keys_out[pos] = key;
-            if constexpr (FINAL) {
-                t_colind[pos] = owner_row(rowptr, m, idx);
-                t_vals[pos] = vals[idx];
-            } else {
-                idx_out[pos] = idx;
+        const long ec = e < n ? e : n - 1;
+        key[r] = keys_in[ec];
+        val[r] = vals_in[ec];
+        if constexpr (!FIRST) row[r] = rows_in[ec];
+    }
+    if constexpr (FIRST) {
+        // rows of the wave's run lie in [row_lo, row_hi]; the 16 searches of a lane advance together
+        // so that their probes overlap
+        int lo[kSortRounds], hi[kSortRounds];
+        const long last = min(wbase + kSortWaveRun - 1, (long)n - 1);
+        int row_lo = 0, row_hi = 0;
+        if (wbase < n) {
+            row_lo = owner_row(rowptr, 0, m - 1, (int)wbase);
+            row_hi = owner_row(rowptr, row_lo, m - 1, (int)last);
+        }
+#pragma unroll
+        for (int r = 0; r < kSortRounds; ++r) { lo[r] = row_lo; hi[r] = row_hi; }
+        for (int span = row_hi - row_lo; span > 0; span >>= 1) {      // ceil(log2(span + 1)) steps
+#pragma unroll
+            for (int r = 0; r < kSortRounds; ++r) {
+                const long e = wbase + r * 64 + lane;
+                const int ec = (int)(e < last ? e : last);
+                const int mid = (lo[r] + hi[r]) >> 1;
+                if (rowptr[mid + 1] > ec) hi[r] = mid; else lo[r] = mid + 1;
             }
         }
+#pragma unroll
+        for (int r = 0; r < kSortRounds; ++r) row[r] = lo[r];
+    }
+    __syncthreads();
+    // digits per wave; the peer masks are kept for the placement step
+    unsigned long long peers[kSortRounds];
+#pragma unroll
+    for (int r = 0; r < kSortRounds; ++r) {
+        const bool valid = wbase + r * 64 + lane < n;
+        const int d = digit_of(key[r], shift, mask);
+        peers[r] = valid ? digit_peers(d, valid) : 0ull;
+        if (valid && lane == __ffsll((long long)peers[r]) - 1) atomicAdd(&wcnt[wave][d], __popcll(peers[r]));
+        __builtin_amdgcn_sched_barrier(0);                // keep the ballots of one round together
+    }
+    __syncthreads();
+    // thread d: counts of digit d -> first tile slot of every (wave, d), and the offset that turns
+    // a tile slot of digit d into its global position
+    {
+        const int d = threadIdx.x;
+        int c[kSortWaves], total = 0;
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) { c[w] = wcnt[w][d]; total += c[w]; }
+        int all;
+        int slot = block_exclusive_scan(total, sh, &all);
+        gbase[d] = hist[(long)d * nblocks + blockIdx.x] - slot;
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) { wcnt[w][d] = slot; slot += c[w]; }
+    }
+    __syncthreads();
+    // stable placement inside the tile: rounds in order, peers ranked by lane number
+#pragma unroll
+    for (int r = 0; r < kSortRounds; ++r) {
+        const bool valid = peers[r] != 0ull;              // a valid lane is its own peer
+        const int d = digit_of(key[r], shift, mask);
+        const int leader = __ffsll((long long)peers[r]) - 1;
+        int first = 0;
+        if (valid && lane == leader) first = atomicAdd(&wcnt[wave][d], __popcll(peers[r]));
+        first = __shfl(first, leader & 63);
+        if (valid) {
+            const int slot = first + __popcll(peers[r] & ((1ull << lane) - 1ull));
+            skey[slot] = key[r];
+            srow[slot] = row[r];
+            sval[slot] = val[r];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    // copy out: neighbouring tile slots of one digit are neighbouring global positions
+    for (int i = threadIdx.x; i < tile_count; i += kSortBlock) {
+        const int k2 = skey[i];
+        const int pos = gbase[digit_of(k2, shift, mask)] + i;
+        keys_out[pos] = k2;
+        rows_out[pos] = srow[i];
+        vals_out[pos] = sval[i];
     }
 }
 
