@@ -330,6 +330,17 @@ def rmat_csr(scale: int, edge_factor: float = 16.0, a: float = 0.57, b: float = 
     return CSR(n, n, rowptr, colind, _uniform_vals(rng, colind.size), name, seed)
 
 
+def reversed_edges(a: CSR, name: str | None = None) -> CSR:
+    """The same graph with every edge reversed (entry (i, j) becomes (j, i), values kept): the matrix
+    a GNN's backward pass multiplies with.  For the power-law generator this turns a few popular
+    columns into a few very long rows, a much harsher row-length distribution than the original."""
+    rows = np.repeat(np.arange(a.m, dtype=np.int64), np.diff(a.rowptr.astype(np.int64)))
+    order = np.lexsort((rows, a.colind))                      # by old column, then old row
+    lens = np.bincount(a.colind, minlength=a.k)
+    return CSR(a.k, a.m, _rowptr_from_lens(lens), rows[order].astype(np.int32), a.vals[order].copy(),
+               name or a.name + "_rev", a.seed)
+
+
 # ----------------------------------------------------------------------------------------------
 # the paper's 5-row illustration
 # ----------------------------------------------------------------------------------------------

@@ -145,7 +145,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--train", nargs="+", required=True)
     ap.add_argument("--eval", nargs="+", required=True)
-    ap.add_argument("--trees", type=int, default=60)
+    ap.add_argument("--trees", type=int, default=120)
     ap.add_argument("--depth", type=int, default=5)
     ap.add_argument("--report", default=os.path.join(PKG, "selector_data", "report.txt"))
     ap.add_argument("--no-write", action="store_true")

@@ -60,6 +60,13 @@ def family_members():
                                      (524288, 10000, 50000))):
         fam.append((f"skewed_m{m}", lambda m=m, lo=lo, hi=hi, i=i: gen.skewed_csr(m=m, heavy_lo=lo, heavy_hi=hi,
                                                                                seed=7300 + i)))
+    # in-link matrices of power-law graphs (a GNN's backward pass) and R-MAT graphs
+    for i, m in enumerate((16384, 65536, 262144)):
+        fam.append((f"powerlaw_rev_m{m}", lambda m=m, i=i: gen.reversed_edges(gen.powerlaw_csr(m=m, seed=7400 + i))))
+    for i, (scale, ef, a, b) in enumerate(((14, 16.0, 0.57, 0.19), (16, 16.0, 0.57, 0.19), (18, 16.0, 0.57, 0.19),
+                                           (16, 32.0, 0.45, 0.15), (17, 8.0, 0.65, 0.15))):
+        fam.append((f"rmat_s{scale}_e{int(ef)}_a{int(a * 100)}",
+                    lambda scale=scale, ef=ef, a=a, b=b, i=i: gen.rmat_csr(scale, ef, a, b, b, seed=7500 + i)))
     return fam
 
 

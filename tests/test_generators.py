@@ -120,3 +120,19 @@ def test_rmat_same_size_and_sparsity_different_dispersion():
     assert stds[0] < stds[1] < stds[2]                           # skewed quadrants -> dispersed rows
     again = gen.rmat_csr(12, 8.0, 0.57, 0.19, 0.19, seed=8102)
     assert np.array_equal(again.colind, g.colind)                 # seeded
+
+
+def test_reversed_edges_is_the_same_edge_set_reversed():
+    a = gen.powerlaw_csr(m=2048, max_len=256, seed=71)
+    t = gen.reversed_edges(a)
+    assert (t.m, t.k, t.nnz) == (a.k, a.m, a.nnz) and t.rowptr[-1] == a.nnz
+    rows_a = np.repeat(np.arange(a.m), np.diff(a.rowptr))
+    rows_t = np.repeat(np.arange(t.m), np.diff(t.rowptr))
+    fwd = sorted(zip(rows_a.tolist(), a.colind.tolist(), a.vals.tolist()))
+    rev = sorted(zip(t.colind.tolist(), rows_t.tolist(), t.vals.tolist()))
+    assert fwd == rev
+    for i in range(t.m):                                   # columns ascend inside every row
+        seg = t.colind[t.rowptr[i]:t.rowptr[i + 1]]
+        assert np.all(np.diff(seg) > 0)
+    # popular columns become rows longer than any row of the original (capped at 256 entries)
+    assert t.row_lengths().max() > 2 * a.row_lengths().max()
