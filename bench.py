@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="input/output copies rotated between steps")
     ap.add_argument("--no-variants", action="store_true", help="skip timing each of the 8 ids")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prepare", action="store_true",
+                    help="skip da_spmm_prepare (the one-off per-matrix chunk schedule of the EB algorithms)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU only (single-GPU kernels, no collectives); use --gpus 1")
@@ -119,6 +121,16 @@ def main():
     feat_ms = (time.perf_counter() - t1) * 1e3
     for c in copies[1:]:                      # every rotated copy is a matrix of its own
         da.da_spmm_features(a.m, N, c["rp"])
+    # one-off per-matrix preparation of the EB algorithms (chunk order), timed separately like a0
+    prep_ms = None
+    if not args.no_prepare:
+        da.da_spmm_prepare(a.m, a.k, a.nnz, copies[0]["rp"], copies[0]["ci"])       # includes first-use costs
+        da.da_spmm_release(copies[0]["rp"])
+        t1 = time.perf_counter()
+        da.da_spmm_prepare(a.m, a.k, a.nnz, copies[0]["rp"], copies[0]["ci"])
+        prep_ms = (time.perf_counter() - t1) * 1e3
+        for c in copies[1:]:
+            da.da_spmm_prepare(a.m, a.k, a.nnz, c["rp"], c["ci"])
     t1 = time.perf_counter()
     for _ in range(1000):
         sel = da.da_spmm_select(feats)
@@ -178,6 +190,7 @@ def main():
                      "kernel": f"da_spmm({da.ALGO_NAMES[chosen]}) incl. EB zero pre-pass",
                      "algorithmic_bytes_per_launch": cbytes},
         "features_ms_once_per_matrix": round(feat_ms, 3), "select_us_per_call": round(select_us, 3),
+        "prepare_ms_once_per_matrix": None if prep_ms is None else round(prep_ms, 3),
     }
     # the same calls captured once in a HIP graph and replayed (no host launch cost per call):
     # what a launch-latency-bound caller can get; reported beside the eager figure, never as `value`

@@ -131,6 +131,37 @@ int da_spmm_select(const da_features *f);
 int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, da_features *out);
 
 /*
+ * Optional per-matrix preparation for the EB algorithms (Sec. 3.2 design M2).  An EB worker owns a
+ * fixed number of consecutive stored entries; which worker takes which chunk does not change the
+ * result, but it decides which rows of B are in flight together.  In a row much longer than a
+ * chunk the sorted column indices make consecutive chunks cover successive column ranges, so
+ * handing the chunks to the workers in the order of their first column index turns the random
+ * gather of B into a sweep from low to high rows: concurrently running workers share a narrow
+ * band of B that stays in the L2 caches.
+ *
+ * da_spmm_prepare builds those orders for the chunk sizes the EB kernels use and keeps them, keyed
+ * by (rowptr, colind, m), in library-owned device memory (about nnz/34 ints) until da_spmm_release
+ * (rowptr == NULL releases every matrix) or until 16 other matrices have been prepared.  Later
+ * da_spmm / da_spmm_ex calls with the same rowptr, colind and m and an EB algorithm id pick the
+ * order up by themselves; results are the same up to fp32 rounding order.  It also records nnz
+ * like da_spmm_features does.  A kernel that finds another nnz on the device than the plan was
+ * built for ignores the plan, so a stale plan costs speed, never correctness; the contents of
+ * colind may change freely.  Allocates and frees temporary device memory, synchronises `stream`.
+ * Not to be called while a da_spmm call on the same matrix is still executing (release likewise).
+ *
+ * da_eb_schedule is the building block: order[u], u = 0 .. ceil(nnz/unit)-1, lists the chunk
+ * numbers (chunk c = stored entries [c*unit, (c+1)*unit)) sorted by colind[c*unit], ties in
+ * ascending chunk number -- deterministic.  Caller workspace as for da_csr_transpose (size from
+ * da_eb_schedule_workspace, 256-byte aligned); enqueues only.
+ */
+int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t *rowptr, const int32_t *colind,
+                    void *stream);
+int da_spmm_release(const int32_t *rowptr);
+int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t *bytes /* host, out */);
+int da_eb_schedule(int64_t k, int64_t nnz, const int32_t *colind, int unit, int32_t *order,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Debug aid: check on the device that the CSR arrays are well formed -- rowptr[0] == 0, rowptr
  * non-decreasing, rowptr[m] == nnz (skipped when nnz is passed as -1), every colind in [0, k).
  * The product kernels trust these properties (Sec. 3.1 takes a valid CSR matrix as given) and a

@@ -13,6 +13,7 @@ Contents (each cites the passage of the paper it follows):
                           pass of the aggregation step of a graph-convolution layer (Sec. 6, GCN)
   csr_transpose           CSR arrays of A^T with ascending indices inside every row
   gcn_layer / gcn_layer_backward   relu(A.(X.W) + b) and its gradients in fp64 (Sec. 6, GCN)
+  eb_schedule             order in which EB workers take their chunks when sorted by first column
   features                input characteristics of Sec. 5.1, Table 2 (nnz, matrix size, standard
                           deviation of row lengths, N) plus mean / max row length
   conditional_reduction   the conditional prefix-sum network of Sec. 4 (EB+RM+PR, Fig. 6(e)),
@@ -210,6 +211,16 @@ def gcn_layer_backward(rowptr, colind, vals, X, W, Z, d_out, relu: bool = True):
         for p in range(rp[i], rp[i + 1]):
             dH[ci[p]] += va[p] * dZ[i]
     return dH @ W.T, X.T @ dH, dZ.sum(axis=0)
+
+
+def eb_schedule(colind, unit: int):
+    """Chunk numbers 0 .. ceil(nnz/unit)-1 of the element-balanced partition (Sec. 3.2: a worker owns
+    `unit` consecutive stored entries) ordered by the column index of each chunk's first entry,
+    ties by chunk number.  Any permutation gives the same product; this one makes concurrently
+    running workers touch neighbouring rows of the dense operand."""
+    colind = np.asarray(colind)
+    first = colind[::unit].astype(np.int64)
+    return np.argsort(first, kind="stable").astype(np.int32)
 
 
 # --------------------------------------------------------------------------------------------

@@ -23,7 +23,8 @@ DA_OK, DA_ERR_INVALID_ARG, DA_ERR_BAD_ALGO, DA_ERR_UNSUPPORTED, DA_ERR_HIP = ran
 DA_NUM_ALGOS = 8
 DA_ROW_MAJOR, DA_COL_MAJOR = 0, 1
 EXPORTS = ("da_spmm", "da_spmm_ex", "da_spmm_select", "da_spmm_features", "da_csr_transpose_workspace",
-           "da_csr_transpose", "da_csr_validate", "da_spmm_algo_name", "da_spmm_last_error")
+           "da_csr_transpose", "da_csr_validate", "da_spmm_prepare", "da_spmm_release",
+           "da_eb_schedule_workspace", "da_eb_schedule", "da_spmm_algo_name", "da_spmm_last_error")
 
 
 class da_features(ctypes.Structure):
@@ -48,6 +49,14 @@ _lib.da_csr_transpose.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp
 _lib.da_csr_transpose.restype = ctypes.c_int
 _lib.da_csr_validate.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp]
 _lib.da_csr_validate.restype = ctypes.c_int
+_lib.da_spmm_prepare.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp]
+_lib.da_spmm_prepare.restype = ctypes.c_int
+_lib.da_spmm_release.argtypes = [_vp]
+_lib.da_spmm_release.restype = ctypes.c_int
+_lib.da_eb_schedule_workspace.argtypes = [_i64, _i64, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+_lib.da_eb_schedule_workspace.restype = ctypes.c_int
+_lib.da_eb_schedule.argtypes = [_i64, _i64, _vp, ctypes.c_int, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.da_eb_schedule.restype = ctypes.c_int
 _lib.da_spmm_algo_name.argtypes = [ctypes.c_int]
 _lib.da_spmm_algo_name.restype = ctypes.c_char_p
 _lib.da_spmm_last_error.argtypes = []
@@ -190,6 +199,36 @@ def da_csr_validate(m, k, nnz, rowptr, colind, stream=None) -> None:
     st = da_csr_validate_status(m, k, nnz, rowptr, colind, stream)
     if st != DA_OK:
         raise DaSpmmError(st, da_spmm_last_error())
+
+
+def _check(st: int) -> None:
+    if st != DA_OK:
+        raise DaSpmmError(st, da_spmm_last_error())
+
+
+def da_spmm_prepare(m, k, nnz, rowptr, colind, stream=None) -> None:
+    """Build and keep the EB chunk orders of this matrix (see include/da_spmm.h)."""
+    _check(int(_lib.da_spmm_prepare(int(m), int(k), int(nnz), _ptr(rowptr), _ptr(colind), _stream(stream))))
+
+
+def da_spmm_release(rowptr=None) -> None:
+    """Drop the prepared orders of one matrix (or of all, with None)."""
+    _check(int(_lib.da_spmm_release(_ptr(rowptr))))
+
+
+def da_eb_schedule_workspace(k, nnz, unit) -> int:
+    out = ctypes.c_size_t(0)
+    _check(int(_lib.da_eb_schedule_workspace(int(k), int(nnz), int(unit), ctypes.byref(out))))
+    return int(out.value)
+
+
+def da_eb_schedule_status(k, nnz, colind, unit, order, workspace, workspace_bytes, stream=None) -> int:
+    return int(_lib.da_eb_schedule(int(k), int(nnz), _ptr(colind), int(unit), _ptr(order), _ptr(workspace),
+                                   int(workspace_bytes), _stream(stream)))
+
+
+def da_eb_schedule(k, nnz, colind, unit, order, workspace, workspace_bytes, stream=None) -> None:
+    _check(da_eb_schedule_status(k, nnz, colind, unit, order, workspace, workspace_bytes, stream))
 
 
 def da_spmm_algo_name(algo: int):

@@ -67,7 +67,10 @@ enum Family { RB_SR, RB_PR, EB_SR, EB_PR };
 struct Geometry {
     int V, G, NV, chunk;
     bool pin;   // pin column tiles to XCDs when the tile count is 2, 4 or 8
+    int stripe; // blocks per stripe when a prepared matrix's chunk order is dealt to the XCDs (0: off)
 };
+
+constexpr int kSweepStripe = 256;
 
 constexpr int kMaxGridY = 65535;
 constexpr int kMaxGroupPR = 8;         // RM mapping under PR keeps at least 8 slots along the entries
@@ -103,6 +106,30 @@ int64_t lookup_nnz(const void* rowptr, int64_t m) {
     return -1;
 }
 
+// Chunk schedules of matrices prepared with da_spmm_prepare, keyed like the nnz hints.  The
+// orders live in one library-owned device allocation per matrix.
+constexpr int kPlanUnits[4] = {64, 128, 256, 512};
+struct Plan {
+    const void* rowptr;
+    const void* colind;
+    int64_t m, nnz;
+    int* order[4];
+    int units[4];
+    void* block;
+};
+std::mutex g_plan_mu;
+Plan g_plans[16];
+int g_plan_next = 0;
+
+Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int chunk) {
+    std::lock_guard<std::mutex> lk(g_plan_mu);
+    for (const auto& pl : g_plans)
+        if (pl.block && pl.rowptr == rowptr && pl.colind == colind && pl.m == m)
+            for (int i = 0; i < 4; ++i)
+                if (kPlanUnits[i] == chunk) return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0};
+    return Schedule{nullptr, 0, 0, 0};
+}
+
 // Default geometry per algorithm family and N.  Measured on MI355X: 16-byte and 4-byte gathers
 // run at full rate, 8-byte gathers at about half, and narrow rows (N < 32) gather fastest with one
 // column per lane.  Setting DA_SPMM_TUNE=1 lets DA_SPMM_V / _G / _NV / _CHUNK override the choice
@@ -113,7 +140,7 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
     // 16-byte accesses need unit column strides and rows that start on 16-byte boundaries
     const bool vec4_ok = (N % 4 == 0) && (addr % 16 == 0) && sd.cb == 1 && sd.cc == 1 &&
                          sd.rb % 4 == 0 && sd.rc % 4 == 0;
-    Geometry g{1, 1, 1, 0, false};
+    Geometry g{1, 1, 1, 0, false, kSweepStripe};
     if (cm) {
         g.V = vec4_ok ? 4 : 1;
         const long vecs = (N + g.V - 1) / g.V;
@@ -132,6 +159,8 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
         g.G = env_int("DA_SPMM_G", g.G);
         g.NV = env_int("DA_SPMM_NV", g.NV);
         g.pin = env_int("DA_SPMM_PIN", g.pin ? 1 : 0) != 0;
+        g.stripe = env_int("DA_SPMM_STRIPE", g.stripe);
+        if (g.stripe < 0 || g.stripe > 4096) return fail(DA_ERR_UNSUPPORTED, "DA_SPMM_STRIPE outside 0..4096%s");
         if ((g.V != 1 && g.V != 4) || (g.V == 4 && !vec4_ok) || !is_pow2(g.G) || g.G > kWave ||
             (pr && g.G > kMaxGroupPR) || (g.NV != 1 && g.NV != 2 && g.NV != 4) || (g.G > 1 && g.NV != 1))
             return fail(DA_ERR_UNSUPPORTED, "DA_SPMM_V/_G/_NV override is not a supported combination%s");
@@ -211,13 +240,32 @@ int launch(Family fam, const Problem& p, const Geometry& geo) {
         // pre-pass: zero the rows that receive atomic additions, and the rows without entries
         const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
         hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.C, chunk);
+        // chunk order of a prepared matrix (column sweep), if one exists for this chunk size
+        Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0) ? Schedule{nullptr, 0, 0, 0}
+                                                         : lookup_schedule(p.rowptr, p.colind, p.m, chunk);
+        if (sch.order && !pin) {
+            // deal the schedule to the XCDs in stripes (sweep_block)
+            // stripe length near geo.stripe such that whole rounds of 8 stripes cover the blocks with
+            // next to no surplus (all XCDs then get the same number of stripes)
+            const long wpb = fam == EB_SR ? (long)kWavesPerBlock * (kWave / G) : (long)kWavesPerBlock;
+            const long nvb = (sch.units + wpb - 1) / wpb;
+            const long per_xcd = (nvb + 7) / 8;
+            if (geo.stripe > 0 && per_xcd >= 2) {
+                long rounds = (per_xcd + geo.stripe / 2) / geo.stripe;
+                if (rounds < 1) rounds = 1;
+                sch.stripe = (int)((per_xcd + rounds - 1) / rounds);
+                const long covered = 8L * sch.stripe * rounds;
+                if (blocks >= nvb) blocks = covered;       // one chunk per worker
+            }
+            blocks = (blocks + 7) / 8 * 8;                 // block b stays on XCD b % 8 on every pass
+        }
         if (fam == EB_SR) {
             hipLaunchKernelGGL((eb_sr_kernel<V, G, NV>), grid_for(blocks), block, 0, p.stream,
-                               p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin);
+                               p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin, sch);
         } else {
             if constexpr (G <= kMaxGroupPR)
                 hipLaunchKernelGGL((eb_pr_kernel<V, G, NV>), grid_for(blocks), block, 0, p.stream,
-                                   p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin);
+                                   p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin, sch);
         }
         break;
     }
@@ -497,6 +545,116 @@ int da_csr_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, c
                        0, s, sorted_keys, n, (int)k, t_rowptr);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "da_csr_transpose launch");
+    return DA_OK;
+}
+
+int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t* bytes)
+{
+    if (!bytes) return fail(DA_ERR_INVALID_ARG, "null bytes%s");
+    if (k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
+    if (k > 0x7ffffffeLL || nnz > 0x7fffffffLL) return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
+    *bytes = plan_transpose(k, (nnz + unit - 1) / unit).bytes;
+    return DA_OK;
+}
+
+int da_eb_schedule(int64_t k, int64_t nnz, const int32_t* colind, int unit, int32_t* order,
+                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
+    if (k > 0x7ffffffeLL || nnz > 0x7fffffffLL) return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
+    if (nnz == 0) return DA_OK;
+    if (!colind || !order) return fail(DA_ERR_INVALID_ARG, "null colind or order%s");
+    const int64_t nunits = (nnz + unit - 1) / unit;
+    const TransposePlan t = plan_transpose(k, nunits);
+    if (!workspace || workspace_bytes < t.bytes)
+        return fail(DA_ERR_INVALID_ARG, "workspace missing or smaller than da_eb_schedule_workspace reports%s");
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+        return fail(DA_ERR_INVALID_ARG, "workspace is not 256-byte aligned%s");
+    hipStream_t s = (hipStream_t)stream;
+    char* ws = static_cast<char*>(workspace);
+    int* keys[2] = {reinterpret_cast<int*>(ws + t.off_keys[0]), reinterpret_cast<int*>(ws + t.off_keys[1])};
+    int* ids[2] = {reinterpret_cast<int*>(ws + t.off_rows[0]), reinterpret_cast<int*>(ws + t.off_rows[1])};
+    float* pad[2] = {reinterpret_cast<float*>(ws + t.off_vals[0]), reinterpret_cast<float*>(ws + t.off_vals[1])};
+    int* hist = reinterpret_cast<int*>(ws + t.off_hist);
+    int* part = reinterpret_cast<int*>(ws + t.off_part);
+    const int n = (int)nunits;
+    hipLaunchKernelGGL(schedule_keys_kernel, dim3((unsigned)((n + kSortBlock - 1) / kSortBlock)), dim3(kSortBlock), 0, s,
+                       colind, unit, n, keys[0], ids[0], pad[0]);
+    const int mask = (1 << t.digit_bits) - 1;
+    for (int p = 0; p < t.passes; ++p) {
+        const int shift = p * t.digit_bits;
+        const int in = p & 1, out = in ^ 1;
+        int* ids_out = p == t.passes - 1 ? order : ids[out];
+        hipLaunchKernelGGL(radix_count_kernel, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys[in], n, shift, mask, hist, t.nblocks);
+        hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
+        hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(kSortBlock), 0, s, part, (int)t.parts);
+        hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
+        hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys[in], ids[in], pad[in], n,
+                           shift, mask, hist, t.nblocks, keys[out], ids_out, pad[out], (const int*)nullptr, 0);
+    }
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "da_eb_schedule launch");
+    return DA_OK;
+}
+
+int da_spmm_release(const int32_t* rowptr)
+{
+    std::lock_guard<std::mutex> lk(g_plan_mu);
+    hipError_t e = hipSuccess;
+    for (auto& pl : g_plans)
+        if (pl.block && (!rowptr || pl.rowptr == rowptr)) {
+            const hipError_t f = hipFree(pl.block);
+            if (f != hipSuccess) e = f;
+            pl = Plan{};
+        }
+    if (e != hipSuccess) return hip_fail(e, "da_spmm_release");
+    return DA_OK;
+}
+
+int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, void* stream)
+{
+    if (m < 0 || k < 0 || nnz < 0) return fail(DA_ERR_INVALID_ARG, "negative size%s");
+    if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
+        return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
+    if (m == 0 || nnz == 0) return DA_OK;
+    if (!rowptr || !colind) return fail(DA_ERR_INVALID_ARG, "null rowptr or colind%s");
+    if (debug_validate()) {
+        const int v = da_csr_validate(m, k, nnz, rowptr, colind, stream);
+        if (v != DA_OK) return v;
+    }
+    Plan pl{};
+    pl.rowptr = rowptr; pl.colind = colind; pl.m = m; pl.nnz = nnz;
+    size_t ints = 0, ws_bytes = 0;
+    for (int i = 0; i < 4; ++i) {
+        pl.units[i] = (int)((nnz + kPlanUnits[i] - 1) / kPlanUnits[i]);
+        ints += (size_t)((pl.units[i] + 63) & ~63);
+        const size_t b = plan_transpose(k, pl.units[i]).bytes;
+        ws_bytes = b > ws_bytes ? b : ws_bytes;
+    }
+    void* ws = nullptr;
+    hipError_t e = hipMalloc(&pl.block, ints * sizeof(int));
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc");
+    e = hipMalloc(&ws, ws_bytes);
+    if (e != hipSuccess) { (void)hipFree(pl.block); return hip_fail(e, "hipMalloc"); }
+    int status = DA_OK;
+    size_t off = 0;
+    for (int i = 0; i < 4 && status == DA_OK; ++i) {
+        pl.order[i] = static_cast<int*>(pl.block) + off;
+        off += (size_t)((pl.units[i] + 63) & ~63);
+        status = da_eb_schedule(k, nnz, colind, kPlanUnits[i], pl.order[i], ws, ws_bytes, stream);
+    }
+    e = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(ws);
+    if (status == DA_OK && e != hipSuccess) status = hip_fail(e, "da_spmm_prepare");
+    if (status != DA_OK) { (void)hipFree(pl.block); return status; }
+    remember_nnz(rowptr, m, nnz);
+    std::lock_guard<std::mutex> lk(g_plan_mu);
+    Plan* slot = nullptr;
+    for (auto& q : g_plans)
+        if (q.block && q.rowptr == rowptr && q.m == m) { slot = &q; break; }      // replace an older plan of this matrix
+    if (!slot) { slot = &g_plans[g_plan_next]; g_plan_next = (g_plan_next + 1) % 16; }
+    if (slot->block) (void)hipFree(slot->block);
+    *slot = pl;
     return DA_OK;
 }
 

@@ -40,6 +40,21 @@ struct Strides {
     long rb, cb, rc, cc;
 };
 
+// Order in which the EB workers take the chunks of stored entries: worker u takes chunk order[u]
+// instead of chunk u.  The order is a permutation of 0..units-1 built for a matrix with `nnz`
+// stored entries and the chunk size of the launch; a kernel that finds another nnz on the device
+// ignores it (order == nullptr: no schedule).
+// stripe > 0: the schedule is dealt to the 8 XCDs in stripes of `stripe` blocks (see sweep_block).
+// The kernel rounds the number of blocks up to whole rounds of 8 stripes (surplus blocks find no
+// chunk), so the host picks a stripe length that makes this surplus small; the grid's x extent must
+// be a multiple of 8 so that a block stays on its XCD when it makes more than one pass.
+struct Schedule {
+    const int* order;
+    int units;
+    int nnz;
+    int stripe;
+};
+
 // ------------------------------------------------------------------------------------------
 // small helpers
 // ------------------------------------------------------------------------------------------
@@ -240,6 +255,16 @@ __device__ __forceinline__ BlockMap block_map(int pin_tiles) {
         b.nbx = (long)(gridDim.x >> 3) * per;
     }
     return b;
+}
+
+// Position in the schedule of (virtual) block vb when the schedule is swept by all XCDs together:
+// workgroups go round-robin to the 8 XCDs, so block vb runs on XCD vb % 8 and is that XCD's
+// (vb / 8)-th block.  Stripe t of XCD x is stripe 8 t + x of the schedule: at any time the XCDs work
+// on 8 neighbouring stripes, each on its own, and the rows of B that one L2 has to hold are an
+// eighth of the band all running workers cover.  A bijection on [0, n) for n a multiple of 8*stripe.
+__device__ __forceinline__ long sweep_block(long vb, int stripe) {
+    const long x = vb & 7, l = vb >> 3;
+    return ((l / stripe) * 8 + x) * stripe + l % stripe;
 }
 
 // Calls f(Count<UU>, t) for t covering [0, cnt) in blocks of UMAX, then 4, 2, 1 entries, so that
@@ -462,7 +487,7 @@ template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
-    int pin_tiles)
+    int pin_tiles, Schedule sch)
 {
     constexpr int GPW = kWave / G;                        // workers per wave
     constexpr int SB = StageBatch<G>::value;
@@ -476,11 +501,18 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     const float* __restrict__ Bn = B + (long)n0 * sd.cb;
     float* __restrict__ Cn = C + (long)n0 * sd.cc;
     const int nnz = rowptr[m];
-    const long nworkers = bm.nbx * kWavesPerBlock * GPW;
-    const long worker = (bm.bx * kWavesPerBlock + wave) * GPW + g;
     int2* st = stage + (G > 1 ? (wave * GPW + g) * SB : 0);
 
-    for (long c0l = worker * chunk; c0l < nnz; c0l += nworkers * chunk) {
+    const long nunits = ((long)nnz + chunk - 1) / chunk;
+    const bool scheduled = sch.order != nullptr && sch.nnz == nnz && sch.units == nunits;
+    const int stripe = (scheduled && pin_tiles <= 0) ? sch.stripe : 0;
+    constexpr long WPB = kWavesPerBlock * GPW;            // workers per block
+    long nvb = (nunits + WPB - 1) / WPB;                  // blocks needed to cover every chunk once
+    if (stripe > 0) nvb = (nvb + 8L * stripe - 1) / (8L * stripe) * (8L * stripe);   // whole rounds of 8 stripes
+    for (long vb = bm.bx; vb < nvb; vb += bm.nbx) {
+        const long u = (stripe > 0 ? sweep_block(vb, stripe) : vb) * WPB + wave * GPW + g;
+        if (u >= nunits) continue;
+        const long c0l = (scheduled ? (long)sch.order[u] : u) * chunk;
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);
         int row = row_of_entry_group<G>(rowptr, 0, m - 1, c0, j, g * G);
@@ -579,7 +611,7 @@ template <int V, int G, int NV>
 __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
-    int pin_tiles)
+    int pin_tiles, Schedule sch)
 {
     constexpr int S = kWave / G;
     constexpr int UU = G < 4 ? G : 4;                     // steps whose gathers are issued together
@@ -592,11 +624,17 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     const float* __restrict__ Bn = B + (long)n0 * sd.cb;
     float* __restrict__ Cn = C + (long)n0 * sd.cc;
     const int nnz = rowptr[m];
-    const long nwaves = bm.nbx * kWavesPerBlock;
-    const long wave_id = bm.bx * kWavesPerBlock + wave;
     int4* st = stage + (G > 1 ? wave * kWave : 0);
 
-    for (long c0l = wave_id * chunk; c0l < nnz; c0l += nwaves * chunk) {
+    const long nunits = ((long)nnz + chunk - 1) / chunk;
+    const bool scheduled = sch.order != nullptr && sch.nnz == nnz && sch.units == nunits;
+    const int stripe = (scheduled && pin_tiles <= 0) ? sch.stripe : 0;
+    long nvb = (nunits + kWavesPerBlock - 1) / kWavesPerBlock;   // blocks needed to cover every chunk once
+    if (stripe > 0) nvb = (nvb + 8L * stripe - 1) / (8L * stripe) * (8L * stripe);   // whole rounds of 8 stripes
+    for (long vb = bm.bx; vb < nvb; vb += bm.nbx) {
+        const long u = (stripe > 0 ? sweep_block(vb, stripe) : vb) * kWavesPerBlock + wave;
+        if (u >= nunits) continue;
+        const long c0l = (scheduled ? (long)sch.order[u] : u) * chunk;
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);
         const int row_lo = row_of_entry_group<kWave>(rowptr, 0, m - 1, c0, lane, 0);

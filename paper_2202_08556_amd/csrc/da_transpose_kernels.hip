@@ -285,6 +285,20 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
     }
 }
 
+// Sort keys of the EB schedule: unit u (the stored entries [u*unit, (u+1)*unit)) is keyed by the
+// column index of its first entry; ids = 0, 1, 2, ...; pad = 0 (the value slot of the triples the
+// radix passes move is not used here).
+__global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(const int* __restrict__ colind, int unit, int nunits,
+                                                                   int* __restrict__ keys, int* __restrict__ ids,
+                                                                   float* __restrict__ pad)
+{
+    const long u = (long)blockIdx.x * kSortBlock + threadIdx.x;
+    if (u >= nunits) return;
+    keys[u] = colind[u * unit];
+    ids[u] = (int)u;
+    pad[u] = 0.f;
+}
+
 // t_rowptr[c] = number of stored entries with column index < c, for c = 0..k.
 __global__ __launch_bounds__(kSortBlock) void rowptr_from_sorted_kernel(const int* __restrict__ keys, int n, int k,
                                                                         int* __restrict__ t_rowptr)

@@ -33,6 +33,7 @@ class SparseGraph:
         self._features = None
         self._algo = {}
         self._t = None
+        self._prepared = False
 
     @classmethod
     def from_numpy(cls, a, device="cuda:0") -> "SparseGraph":
@@ -40,6 +41,13 @@ class SparseGraph:
         dev = torch.device(device)
         return cls(a.m, a.k, torch.from_numpy(a.rowptr).to(dev), torch.from_numpy(a.colind).to(dev),
                    torch.from_numpy(a.vals).to(dev))
+
+    def __del__(self):
+        if getattr(self, "_prepared", False):
+            try:
+                da.da_spmm_release(self.rowptr)
+            except Exception:
+                pass
 
     def features(self, N: int) -> dict:
         if self._features is None:
@@ -77,6 +85,9 @@ class SparseGraph:
             raise ValueError("X must be a float32 k x N tensor")
         X = X.contiguous()
         N = int(X.shape[1])
+        if not self._prepared:                      # one-off: chunk order for the EB algorithms
+            da.da_spmm_prepare(self.m, self.k, self.nnz, self.rowptr, self.colind)
+            self._prepared = True
         C = torch.empty((self.m, N), dtype=torch.float32, device=X.device)
         da.da_spmm(self.m, self.k, N, self.rowptr, self.colind, self.vals, X, C,
                    self.algo_for(N) if algo is None else algo)

@@ -31,6 +31,7 @@ def time_all(graph: gcn.SparseGraph, N: int, seed: int):
     g.manual_seed(seed)
     Bs = [torch.empty((graph.k, N), device=dev).normal_(generator=g) for _ in range(COPIES)]
     Cs = [torch.empty((graph.m, N), device=dev) for _ in range(COPIES)]
+    graph.spmm(Bs[0])                               # makes sure the matrix is prepared
     runs = [da.PreparedSpmm(graph.m, graph.k, N, graph.rowptr, graph.colind, graph.vals, Bs[i], Cs[i])
             for i in range(COPIES)]
     times = []

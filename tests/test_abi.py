@@ -21,7 +21,7 @@ from paper_2202_08556_amd import binding as da  # noqa: E402
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "da_spmm.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(da_(?:spmm|csr)\w*)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(da_(?:spmm|csr|eb)\w*)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():

@@ -1,6 +1,7 @@
 """Parity at the full benchmark sizes, in the launch configuration bench.py times (default geometry,
-nnz hint primed by da_spmm_features): every algorithm id on every named configuration, checked on a
-seeded sample of rows plus the longest rows, which the oracle computes one by one."""
+nnz hint primed by da_spmm_features, matrix prepared with da_spmm_prepare): every algorithm id on
+every named configuration, checked on a seeded sample of rows plus the longest rows, which the
+oracle computes one by one."""
 import numpy as np
 import pytest
 import torch
@@ -25,6 +26,7 @@ def check_all(a, B, label):
     prob = DeviceProblem(a, B)
     feats = da.da_spmm_features(a.m, prob.N, prob.rowptr)      # as bench.py does: primes the nnz hint
     assert feats["nnz"] == a.nnz
+    da.da_spmm_prepare(a.m, a.k, a.nnz, prob.rowptr, prob.colind)   # and builds the EB chunk order
     rows = sample_rows(a)
     c_ref, s_abs = orc.spmm_rows(rows, a.rowptr, a.colind, a.vals, B)
     worst = 0.0
@@ -35,6 +37,7 @@ def check_all(a, B, label):
         assert ratio <= 1.0, f"{label} algo={algo}: tolerance ratio {ratio}"
         assert np.isfinite(c).all(), f"{label} algo={algo}: non-finite output"
         worst = max(worst, ratio)
+    da.da_spmm_release(prob.rowptr)
     return worst
 
 

@@ -172,3 +172,72 @@ def test_graph_conv_layer_matches_fp64_layer():
     assert np.max(np.abs(got - ref_out)) <= 2e-5 * np.max(np.abs(ref_out)) + 1e-6
     for g, r in ((Xd.grad, dX), (layer.weight.grad, dW), (layer.bias.grad, db)):
         assert np.max(np.abs(g.cpu().numpy() - r)) <= 5e-5 * np.max(np.abs(r)) + 1e-6
+
+
+# ---- EB chunk schedule (da_eb_schedule, da_spmm_prepare) -------------------------------------
+def schedule_cases():
+    yield gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001), (64, 256, 512)
+    yield gen.powerlaw_csr(m=8192, seed=2001), (64, 128)
+    yield gen.uniform_csr(m=5000, k=1200000, mean_len=20, seed=51), (1, 64)
+    yield gen.uniform_csr(m=37, k=53, mean_len=5, seed=31), (7, 512)
+
+
+@pytest.mark.parametrize("a,units", list(schedule_cases()), ids=lambda x: getattr(x, "name", None))
+def test_eb_schedule_matches_oracle(a, units):
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    ci = torch.from_numpy(a.colind).to(dev)
+    nnz = int(a.colind.size)
+    for unit in units:
+        print(f"schedule case {a.name} unit={unit}", flush=True)
+        nunits = -(-nnz // unit)
+        order = torch.full((nunits,), -3, dtype=torch.int32, device=dev)
+        nbytes = da.da_eb_schedule_workspace(a.k, nnz, unit)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        da.da_eb_schedule(a.k, nnz, ci, unit, order, ws, nbytes)
+        torch.cuda.synchronize()
+        assert np.array_equal(order.cpu().numpy(), orc.eb_schedule(a.colind, unit))
+    assert da.da_eb_schedule_status(a.k, nnz, ci, 64, order, ws, 8) == da.DA_ERR_INVALID_ARG
+    assert da.da_eb_schedule_status(a.k, nnz, ci, 0, order, ws, nbytes) == da.DA_ERR_INVALID_ARG
+
+
+PREPARED = [("skewed", lambda: gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001), [8, 64]),
+            ("powerlaw", lambda: gen.powerlaw_csr(m=8192, seed=2001), [32, 128]),
+            ("one_long_row", lambda: gen.skewed_csr(m=64, k=40000, heavy_frac=0.02, heavy_lo=30000, heavy_hi=30000,
+                                                    light_mean=0.5, seed=9), [8])]
+
+
+@pytest.mark.parametrize("name,make,Ns", PREPARED, ids=[p[0] for p in PREPARED])
+def test_prepared_matrix_all_algorithms_match_oracle(name, make, Ns):
+    """After da_spmm_prepare the EB ids run with the column-sweep chunk order; every id must still
+    match the oracle, also on the integer twin bit for bit, and also after the plan went stale."""
+    from paper_2202_08556_amd import binding as da
+    from tests.gpu_util import DeviceProblem
+    a = make()
+    try:
+        for N in Ns:
+            B = gen.dense(a.k, N, "uniform", seed=a.seed + N)
+            c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
+            prob = DeviceProblem(a, B)
+            da.da_spmm_prepare(a.m, a.k, a.nnz, prob.rowptr, prob.colind)
+            for algo in range(8):
+                print(f"prepared case {name} N={N} algo={algo}", flush=True)
+                assert orc.tolerance_ratio(prob.run(algo), c_ref, s_abs) <= 1.0, (name, N, algo)
+            # stale plan: other contents (fewer entries) in the same buffers
+            half = gen.CSR(m=a.m, k=a.k, rowptr=np.minimum(a.rowptr, a.rowptr[a.m // 2]).astype(np.int32),
+                           colind=a.colind, vals=a.vals, seed=a.seed, name="half")
+            prob.rowptr.copy_(torch.from_numpy(half.rowptr))
+            c_half, s_half = orc.spmm(half.rowptr, half.colind[:half.rowptr[-1]], half.vals[:half.rowptr[-1]], B)
+            for algo in (4, 5, 6, 7):
+                print(f"stale plan case {name} N={N} algo={algo}", flush=True)
+                assert orc.tolerance_ratio(prob.run(algo), c_half, s_half) <= 1.0, (name, N, algo)
+            da.da_spmm_release(prob.rowptr)
+        ai = gen.integer_twin(a)
+        Bi = gen.dense_int(a.k, Ns[0], seed=3)
+        c_int, _ = orc.spmm(ai.rowptr, ai.colind, ai.vals, Bi, want_abs=False)
+        prob = DeviceProblem(ai, Bi)
+        da.da_spmm_prepare(ai.m, ai.k, ai.nnz, prob.rowptr, prob.colind)
+        for algo in (4, 5, 6, 7):
+            assert orc.bit_mismatches(prob.run(algo), c_int) == 0, (name, algo)
+    finally:
+        da.da_spmm_release()

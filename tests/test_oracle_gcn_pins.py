@@ -157,3 +157,15 @@ def test_gcn_layer_forward_and_gradients():
             args_m[which][idx] -= h
             fd = (loss(*args_p) - loss(*args_m)) / (2 * h)
             assert abs(fd - grad[idx]) < 1e-6 * max(1.0, abs(grad[idx]))
+
+
+# T7 -- the chunk order: a permutation, keys ascending, ties by chunk number; against Python's
+#       tuple sort ---------------------------------------------------------------------------
+@pytest.mark.parametrize("unit", [1, 4, 7, 64])
+def test_eb_schedule_is_sorted_permutation(unit):
+    a = gen.skewed_csr(m=400, k=300, heavy_frac=0.02, heavy_lo=100, heavy_hi=250, seed=45)
+    order = orc.eb_schedule(a.colind, unit)
+    nunits = -(-a.colind.size // unit)
+    assert sorted(order.tolist()) == list(range(nunits))
+    expect = [c for _, c in sorted((int(a.colind[c * unit]), c) for c in range(nunits))]
+    assert order.tolist() == expect
