@@ -204,7 +204,12 @@ def test_eb_schedule_matches_oracle(a, units):
 PREPARED = [("skewed", lambda: gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001), [8, 64]),
             ("powerlaw", lambda: gen.powerlaw_csr(m=8192, seed=2001), [32, 128]),
             ("one_long_row", lambda: gen.skewed_csr(m=64, k=40000, heavy_frac=0.02, heavy_lo=30000, heavy_hi=30000,
-                                                    light_mean=0.5, seed=9), [8])]
+                                                    light_mean=0.5, seed=9), [8]),
+            # several column tiles (520 = 2*256 + 8), a ragged N without 16-byte accesses, and enough
+            # chunks for several rounds of XCD stripes at the smallest chunk size
+            ("wide_and_ragged_N", lambda: gen.skewed_csr(m=20000, k=15000, heavy_frac=0.01, heavy_lo=4000,
+                                                         heavy_hi=9000, seed=12), [520, 13]),
+            ("few_entries", lambda: gen.uniform_csr(m=9, k=11, mean_len=3, seed=5), [4])]
 
 
 @pytest.mark.parametrize("name,make,Ns", PREPARED, ids=[p[0] for p in PREPARED])
@@ -241,3 +246,24 @@ def test_prepared_matrix_all_algorithms_match_oracle(name, make, Ns):
             assert orc.bit_mismatches(prob.run(algo), c_int) == 0, (name, algo)
     finally:
         da.da_spmm_release()
+
+
+def test_prepare_edge_cases_and_release():
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    a = gen.uniform_csr(m=300, k=200, mean_len=6, seed=61)
+    rp, ci = torch.from_numpy(a.rowptr).to(dev), torch.from_numpy(a.colind).to(dev)
+    da.da_spmm_prepare(0, 5, 0, None, None)                        # nothing to prepare
+    da.da_spmm_prepare(a.m, a.k, 0, rp, ci)
+    with pytest.raises(da.DaSpmmError):
+        da.da_spmm_prepare(a.m, a.k, a.nnz, None, ci)
+    with pytest.raises(da.DaSpmmError):
+        da.da_spmm_prepare(-1, a.k, a.nnz, rp, ci)
+    for _ in range(20):                                            # more plans than the table holds: old ones are freed
+        r2 = rp.clone()
+        da.da_spmm_prepare(a.m, a.k, a.nnz, r2, ci)
+    da.da_spmm_prepare(a.m, a.k, a.nnz, rp, ci)
+    da.da_spmm_prepare(a.m, a.k, a.nnz, rp, ci)                    # preparing twice replaces the plan
+    da.da_spmm_release(rp)
+    da.da_spmm_release(rp)                                         # releasing an unknown matrix is not an error
+    da.da_spmm_release()
