@@ -149,7 +149,9 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
     } else {
         g.V = (vec4_ok && N >= 32) ? 4 : 1;
         g.G = pow2_ceil((N + g.V - 1) / g.V);
-        const int cap = pr ? kMaxGroupPR : kWave;
+        // SR: at most 128 columns per tile (32 lanes of 4): at N = 256 two passes over 512-byte row
+        // segments keep more rows of B in L2 than one pass over 1 KB rows and were never slower
+        const int cap = pr ? kMaxGroupPR : (g.V == 4 ? 32 : kWave);
         if (g.G > cap) g.G = cap;
         g.NV = 1;
     }
