@@ -31,6 +31,7 @@ def time_all(a, N, col_major=False):
     dev = torch.device("cuda:0")
     rp, ci, va = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals))
     da.da_spmm_features(a.m, N, rp)
+    da.da_spmm_prepare(a.m, a.k, a.nnz, rp, ci)                 # EB chunk order, as a user would
     g = torch.Generator(device=dev)
     g.manual_seed(a.seed * 1000 + N)
     Bs = [torch.empty((a.k, N), device=dev).uniform_(-1.0, 1.0, generator=g) for _ in range(COPIES)]
@@ -41,6 +42,7 @@ def time_all(a, N, col_major=False):
     for algo in range(da.DA_NUM_ALGOS):
         t, _ = time_algo(lambda i, algo=algo: runs[i % COPIES](algo))
         times.append(t)
+    da.da_spmm_release(rp)
     return np.array(times)
 
 
