@@ -189,8 +189,8 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
     return DA_OK;
 }
 
-template <int V, int G, int NV>
-int launch(Family fam, const Problem& p, const Geometry& geo) {
+template <int V, int G, int NV, bool WIDE>
+int launch_w(Family fam, const Problem& p, const Geometry& geo) {
     const int chunk = geo.chunk;
     const long tile_cols = (long)G * V * NV;
     const long tiles_l = (p.N + tile_cols - 1) / tile_cols;
@@ -206,13 +206,13 @@ int launch(Family fam, const Problem& p, const Geometry& geo) {
     switch (fam) {
     case RB_SR: {
         const long rows_per_block = (long)kWavesPerBlock * (kWave / G);
-        hipLaunchKernelGGL((rb_sr_kernel<V, G, NV>), grid_for((p.m + rows_per_block - 1) / rows_per_block),
+        hipLaunchKernelGGL((rb_sr_kernel<V, G, NV, WIDE>), grid_for((p.m + rows_per_block - 1) / rows_per_block),
                            block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, pin);
         break;
     }
     case RB_PR: {
         if constexpr (G <= kMaxGroupPR) {
-            hipLaunchKernelGGL((rb_pr_kernel<V, G, NV>), grid_for((p.m + kWavesPerBlock - 1) / kWavesPerBlock),
+            hipLaunchKernelGGL((rb_pr_kernel<V, G, NV, WIDE>), grid_for((p.m + kWavesPerBlock - 1) / kWavesPerBlock),
                                block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, pin);
         }
         break;
@@ -262,11 +262,11 @@ int launch(Family fam, const Problem& p, const Geometry& geo) {
             blocks = (blocks + 7) / 8 * 8;                 // block b stays on XCD b % 8 on every pass
         }
         if (fam == EB_SR) {
-            hipLaunchKernelGGL((eb_sr_kernel<V, G, NV>), grid_for(blocks), block, 0, p.stream,
+            hipLaunchKernelGGL((eb_sr_kernel<V, G, NV, WIDE>), grid_for(blocks), block, 0, p.stream,
                                p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin, sch);
         } else {
             if constexpr (G <= kMaxGroupPR)
-                hipLaunchKernelGGL((eb_pr_kernel<V, G, NV>), grid_for(blocks), block, 0, p.stream,
+                hipLaunchKernelGGL((eb_pr_kernel<V, G, NV, WIDE>), grid_for(blocks), block, 0, p.stream,
                                    p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin, sch);
         }
         break;
@@ -275,6 +275,17 @@ int launch(Family fam, const Problem& p, const Geometry& geo) {
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
     return DA_OK;
+}
+
+// 32-bit gather offsets (BRows<false>) need column indices below 2^24, a row pitch below 16 MiB and
+// every element of B within 4 GiB of its base; anything larger takes the 64-bit kernels.
+template <int V, int G, int NV>
+int launch(Family fam, const Problem& p, const Geometry& geo) {
+    const unsigned long long last = (unsigned long long)(p.k > 0 ? p.k - 1 : 0) * (unsigned long long)p.sd.rb +
+                                    (unsigned long long)(p.N > 0 ? p.N - 1 : 0) * (unsigned long long)p.sd.cb;
+    const bool narrow = p.k <= (1 << 24) && p.sd.rb * 4 < (1 << 24) && (last + 4) * 4 < (1ull << 32) &&
+                        env_int("DA_SPMM_WIDE", 0) == 0;
+    return narrow ? launch_w<V, G, NV, false>(fam, p, geo) : launch_w<V, G, NV, true>(fam, p, geo);
 }
 
 template <int V>

@@ -143,6 +143,36 @@ __device__ __forceinline__ int valid_vectors(int n0, int N) {
     return left < 0 ? 0 : (left > NV ? NV : left);
 }
 
+// Address of the lane's first column in a row of B.  The gather address is the only per-entry
+// integer work of the kernels, and in 64-bit form (sign extension, 64 x 64-bit multiply, 64-bit
+// adds: about ten VALU operations, several of them quarter rate) it costs more issue slots than the
+// four multiply-adds a 16-byte gather feeds.  WIDE = false: k < 2^24, row pitch < 16 MiB and B
+// smaller than 4 GiB (checked by the host): byte offset = col * pitch + lane offset in one 24-bit
+// multiply-add, added to the wave-uniform base by the load instruction itself.
+template <bool WIDE>
+struct BRows {
+    const float* base;
+    long rb;
+    unsigned pitch_bytes, lane_bytes;
+    __device__ __forceinline__ BRows(const float* __restrict__ B, int n0, const Strides& sd) {
+        if constexpr (WIDE) {
+            base = B + (long)n0 * sd.cb; rb = sd.rb; pitch_bytes = 0; lane_bytes = 0;
+        } else {
+            base = B; rb = 0;
+            pitch_bytes = (unsigned)sd.rb * 4u;
+            lane_bytes = (unsigned)n0 * (unsigned)sd.cb * 4u;
+        }
+    }
+    __device__ __forceinline__ const float* row(int col) const {
+        if constexpr (WIDE) {
+            return base + (long)col * rb;
+        } else {
+            const unsigned off = __umul24((unsigned)col, pitch_bytes) + lane_bytes;
+            return reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + off);
+        }
+    }
+};
+
 // Orders LDS traffic of the lanes of one wave: the LDS unit serves one wave's requests in issue
 // order, so only the compiler has to be kept from moving accesses across this point.
 __device__ __forceinline__ void wave_lds_sync() {
@@ -285,7 +315,7 @@ __device__ __forceinline__ void for_blocks(int cnt, F&& f) {
 // entries with coalesced requests and pass them round through LDS, so that every entry is fetched
 // once and reused for all columns of the tile (the sparse-element cache of Sec. 4).
 // ------------------------------------------------------------------------------------------
-template <int V, int G, int NV>
+template <int V, int G, int NV, bool WIDE>
 __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
     int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int pin_tiles)
@@ -304,7 +334,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
     if (row < m) { start = rowptr[row]; end = rowptr[row + 1]; }
     Acc<V, NV> acc;
     acc.clear();
-    const float* __restrict__ Bn = B + (long)n0 * sd.cb;
+    const BRows<WIDE> brow(B, n0, sd);
 
     if constexpr (G == 1) {
         if (nvec > 0) {
@@ -317,7 +347,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
 #pragma unroll
                 for (int u = 0; u < UU; ++u) { c[u] = colind[p0 + u]; a[u] = vals[p0 + u]; }
 #pragma unroll
-                for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)c[u] * sd.rb, nvec, sd.cb);
+                for (int u = 0; u < UU; ++u) b[u].load(brow.row(c[u]), nvec, sd.cb);
 #pragma unroll
                 for (int u = 0; u < UU; ++u) acc.fma(a[u], b[u]);
             });
@@ -338,7 +368,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
 #pragma unroll
                     for (int u = 0; u < UU; ++u) e[u] = st[t + u];
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * sd.rb, nvec, sd.cb);
+                    for (int u = 0; u < UU; ++u) b[u].load(brow.row(e[u].x), nvec, sd.cb);
 #pragma unroll
                     for (int u = 0; u < UU; ++u) acc.fma(__int_as_float(e[u].y), b[u]);
                 });
@@ -356,7 +386,7 @@ __global__ __launch_bounds__(kBlock) void rb_sr_kernel(
 // shared through LDS (technique 3), and the slots are combined by a reduction tree (Sec. 3.4 K2).
 // In a batch of 64 staged entries slot s takes entries s, s+S, s+2S, ...
 // ------------------------------------------------------------------------------------------
-template <int V, int G, int NV>
+template <int V, int G, int NV, bool WIDE>
 __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
     int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int pin_tiles)
@@ -374,7 +404,7 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
     const int start = rowptr[row], end = rowptr[row + 1];
     Acc<V, NV> acc;
     acc.clear();
-    const float* __restrict__ Bn = B + (long)n0 * sd.cb;
+    const BRows<WIDE> brow(B, n0, sd);
 
     if constexpr (G == 1) {
         if (nvec > 0) {
@@ -389,14 +419,14 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 #pragma unroll
                 for (int u = 0; u < UU; ++u) { c[u] = colind[p0 + u * kWave]; a[u] = vals[p0 + u * kWave]; }
 #pragma unroll
-                for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)c[u] * sd.rb, nvec, sd.cb);
+                for (int u = 0; u < UU; ++u) b[u].load(brow.row(c[u]), nvec, sd.cb);
 #pragma unroll
                 for (int u = 0; u < UU; ++u) acc.fma(a[u], b[u]);
             });
             const int p = start + (len / kWave) * kWave + lane;
             if (p < end) {
                 Acc<V, NV> b;
-                b.load(Bn + (long)colind[p] * sd.rb, nvec, sd.cb);
+                b.load(brow.row(colind[p]), nvec, sd.cb);
                 acc.fma(vals[p], b);
             }
         }
@@ -417,7 +447,7 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 #pragma unroll
                     for (int u = 0; u < UU; ++u) ee[u] = st[(t + u) * S + s];
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)ee[u].x * sd.rb, nvec, sd.cb);
+                    for (int u = 0; u < UU; ++u) b[u].load(brow.row(ee[u].x), nvec, sd.cb);
 #pragma unroll
                     for (int u = 0; u < UU; ++u) acc.fma(__int_as_float(ee[u].y), b[u]);
                 });
@@ -425,7 +455,7 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
                 if (t < cnt) {
                     const int2 ee = st[t];
                     Acc<V, NV> b;
-                    b.load(Bn + (long)ee.x * sd.rb, nvec, sd.cb);
+                    b.load(brow.row(ee.x), nvec, sd.cb);
                     acc.fma(__int_as_float(ee.y), b);
                 }
             }
@@ -483,7 +513,7 @@ __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
 // named there).  Workers stride over the chunks so that the grid size does not depend on nnz,
 // which only the device knows.
 // ------------------------------------------------------------------------------------------
-template <int V, int G, int NV>
+template <int V, int G, int NV, bool WIDE>
 __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
@@ -498,7 +528,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     const BlockMap bm = block_map(pin_tiles);
     const int n0 = (bm.tile * G + j) * V * NV;
     const int nvec = valid_vectors<V, NV>(n0, N);
-    const float* __restrict__ Bn = B + (long)n0 * sd.cb;
+    const BRows<WIDE> brow(B, n0, sd);
     float* __restrict__ Cn = C + (long)n0 * sd.cc;
     const int nnz = rowptr[m];
     int2* st = stage + (G > 1 ? (wave * GPW + g) * SB : 0);
@@ -540,7 +570,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
                 }
                 if (nvec > 0) {
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * sd.rb, nvec, sd.cb);
+                    for (int u = 0; u < UU; ++u) b[u].load(brow.row(e[u].x), nvec, sd.cb);
                 }
                 if (row_end > q0 + t + UU) {
                     // the common case: the whole block lies inside the current row
@@ -607,7 +637,7 @@ __device__ __forceinline__ Acc<V, NV> slots_allreduce(Acc<V, NV> x) {
     return x;
 }
 
-template <int V, int G, int NV>
+template <int V, int G, int NV, bool WIDE>
 __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
@@ -621,7 +651,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     const BlockMap bm = block_map(pin_tiles);
     const int n0 = (bm.tile * G + j) * V * NV;
     const int nvec = valid_vectors<V, NV>(n0, N);
-    const float* __restrict__ Bn = B + (long)n0 * sd.cb;
+    const BRows<WIDE> brow(B, n0, sd);
     float* __restrict__ Cn = C + (long)n0 * sd.cc;
     const int nnz = rowptr[m];
     int4* st = stage + (G > 1 ? wave * kWave : 0);
@@ -673,7 +703,7 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                 // branch-free gathers: slots past the end of the chunk hold column 0
                 if (nvec > 0) {
 #pragma unroll
-                    for (int u = 0; u < UU; ++u) b[u].load(Bn + (long)e[u].x * sd.rb, nvec, sd.cb);
+                    for (int u = 0; u < UU; ++u) b[u].load(brow.row(e[u].x), nvec, sd.cb);
                 }
                 // all products first: no store or atomic is issued while a gather is outstanding
                 // (stores share the in-order memory counter with loads)

@@ -316,3 +316,18 @@ def test_validate_catches_malformed_csr_and_debug_switch_guards_the_product(monk
     torch.cuda.synchronize()
     c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, Bn)
     assert orc.tolerance_ratio(C.cpu().numpy(), c_ref, s_abs) <= 1.0
+
+
+def test_wide_address_kernels_match_oracle(gpu, monkeypatch):
+    """Operands beyond 4 GiB (or k >= 2^24) take kernels with 64-bit gather addresses; the switch
+    DA_SPMM_WIDE=1 forces them on small inputs so that they are checked here too."""
+    monkeypatch.setenv("DA_SPMM_WIDE", "1")
+    for a, N in ((gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001), 64),
+                 (gen.uniform_csr(m=1237, k=911, mean_len=11, seed=7), 20),
+                 (gen.powerlaw_csr(m=8192, seed=2001), 128)):
+        B = gen.dense(a.k, N, "uniform", seed=a.seed + N)
+        c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
+        prob = gpu(a, B)
+        for algo in ALGOS:
+            print(f"wide case {a.name} N={N} algo={algo}", flush=True)
+            assert orc.tolerance_ratio(prob.run(algo), c_ref, s_abs) <= 1.0, (a.name, N, algo)
