@@ -293,8 +293,9 @@ __device__ __forceinline__ BlockMap block_map(int pin_tiles) {
 // on 8 neighbouring stripes, each on its own, and the rows of B that one L2 has to hold are an
 // eighth of the band all running workers cover.  A bijection on [0, n) for n a multiple of 8*stripe.
 __device__ __forceinline__ long sweep_block(long vb, int stripe) {
-    const long x = vb & 7, l = vb >> 3;
-    return ((l / stripe) * 8 + x) * stripe + l % stripe;
+    const unsigned x = (unsigned)vb & 7u, l = (unsigned)(vb >> 3), st = (unsigned)stripe;   // block counts fit 32 bits
+    const unsigned t = l / st;
+    return (long)(t * 8u + x) * st + (l - t * st);
 }
 
 // Calls f(Count<UU>, t) for t covering [0, cnt) in blocks of UMAX, then 4, 2, 1 entries, so that
@@ -533,12 +534,15 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     const int nnz = rowptr[m];
     int2* st = stage + (G > 1 ? (wave * GPW + g) * SB : 0);
 
-    const long nunits = ((long)nnz + chunk - 1) / chunk;
+    const long nunits = ((unsigned)nnz + (unsigned)chunk - 1u) / (unsigned)chunk;   // nnz < 2^31
     const bool scheduled = sch.order != nullptr && sch.nnz == nnz && sch.units == nunits;
     const int stripe = (scheduled && pin_tiles <= 0) ? sch.stripe : 0;
     constexpr long WPB = kWavesPerBlock * GPW;            // workers per block
     long nvb = (nunits + WPB - 1) / WPB;                  // blocks needed to cover every chunk once
-    if (stripe > 0) nvb = (nvb + 8L * stripe - 1) / (8L * stripe) * (8L * stripe);   // whole rounds of 8 stripes
+    if (stripe > 0) {                                     // whole rounds of 8 stripes
+        const unsigned round = 8u * (unsigned)stripe;
+        nvb = (long)(((unsigned)nvb + round - 1) / round) * round;
+    }
     for (long vb = bm.bx; vb < nvb; vb += bm.nbx) {
         const long u = (stripe > 0 ? sweep_block(vb, stripe) : vb) * WPB + wave * GPW + g;
         if (u >= nunits) continue;
@@ -656,11 +660,14 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     const int nnz = rowptr[m];
     int4* st = stage + (G > 1 ? wave * kWave : 0);
 
-    const long nunits = ((long)nnz + chunk - 1) / chunk;
+    const long nunits = ((unsigned)nnz + (unsigned)chunk - 1u) / (unsigned)chunk;   // nnz < 2^31
     const bool scheduled = sch.order != nullptr && sch.nnz == nnz && sch.units == nunits;
     const int stripe = (scheduled && pin_tiles <= 0) ? sch.stripe : 0;
     long nvb = (nunits + kWavesPerBlock - 1) / kWavesPerBlock;   // blocks needed to cover every chunk once
-    if (stripe > 0) nvb = (nvb + 8L * stripe - 1) / (8L * stripe) * (8L * stripe);   // whole rounds of 8 stripes
+    if (stripe > 0) {                                     // whole rounds of 8 stripes
+        const unsigned round = 8u * (unsigned)stripe;
+        nvb = (long)(((unsigned)nvb + round - 1) / round) * round;
+    }
     for (long vb = bm.bx; vb < nvb; vb += bm.nbx) {
         const long u = (stripe > 0 ? sweep_block(vb, stripe) : vb) * kWavesPerBlock + wave;
         if (u >= nunits) continue;
