@@ -1,6 +1,6 @@
 """Controlled experiments of the paper's Sec. 6.3 on seeded R-MAT matrices (one GPU).
 
-    python -m paper_2202_08556_amd.controlled > gpurun_out/controlled.txt
+    python -m paper_2202_08556_amd.controlled > results/controlled.txt
 
   RB-EB  three matrices of identical size and sparsity whose rows are more and more dispersed
          (R-MAT quadrant probabilities from uniform to strongly skewed): best RB id against best EB id

@@ -1,7 +1,7 @@
 """GCN aggregation as a second workload (the application of the paper's Sec. 6): forward A.X and
 backward A^T.dY on the power-law graph of the headline benchmark, feature lengths 16 ... 256.
 
-    python -m paper_2202_08556_amd.gcn_bench [--m 262144] [--out gpurun_out/gcn_bench.txt]
+    python -m paper_2202_08556_amd.gcn_bench [--m 262144] [--out results/gcn_bench.txt]
 
 For every feature length: time of each of the 8 algorithm ids and of the selector's choice, for
 A (forward) and for A^T (backward); the one-off cost of da_csr_transpose; and one two-layer GCN

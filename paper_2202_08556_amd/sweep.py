@@ -1,9 +1,9 @@
 """Time all 8 algorithm ids on families of seeded matrices: the data the selector is trained and
 scored on (paper Sec. 5: every design is run on every matrix, the model learns which one wins).
 
-    python -m paper_2202_08556_amd.sweep --set eval  --members 0-63  --out gpurun_out/sweep_eval.jsonl
-    python -m paper_2202_08556_amd.sweep --set train --members 0-255 --out gpurun_out/sweep_train.jsonl
-    python -m paper_2202_08556_amd.sweep --set families --out gpurun_out/sweep_families.jsonl
+    python -m paper_2202_08556_amd.sweep --set eval  --members 0-63  --out results/sweep_eval.jsonl
+    python -m paper_2202_08556_amd.sweep --set train --members 0-255 --out results/sweep_train.jsonl
+    python -m paper_2202_08556_amd.sweep --set families --out results/sweep_families.jsonl
 
 Sets
   eval      the 64-member selector sweep (seed base 5000), never trained on
