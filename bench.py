@@ -118,9 +118,12 @@ def main():
     # a0: features, once per matrix (timed separately)
     t1 = time.perf_counter()
     feats = da.da_spmm_features(a.m, N, copies[0]["rp"])
-    feat_ms = (time.perf_counter() - t1) * 1e3
+    feat_first_ms = (time.perf_counter() - t1) * 1e3      # includes loading the kernels on first use
+    feat_ms = feat_first_ms
     for c in copies[1:]:                      # every rotated copy is a matrix of its own
+        t1 = time.perf_counter()
         da.da_spmm_features(a.m, N, c["rp"])
+        feat_ms = (time.perf_counter() - t1) * 1e3
     # one-off per-matrix preparation of the EB algorithms (chunk order), timed separately like a0
     prep_ms = None
     if not args.no_prepare:
@@ -189,7 +192,8 @@ def main():
                      "traffic": measured_traffic(args.workload, N, da.ALGO_NAMES[chosen]),
                      "kernel": f"da_spmm({da.ALGO_NAMES[chosen]}) incl. EB zero pre-pass",
                      "algorithmic_bytes_per_launch": cbytes},
-        "features_ms_once_per_matrix": round(feat_ms, 3), "select_us_per_call": round(select_us, 3),
+        "features_ms_once_per_matrix": round(feat_ms, 3), "features_ms_first_call": round(feat_first_ms, 3),
+        "select_us_per_call": round(select_us, 3),
         "prepare_ms_once_per_matrix": None if prep_ms is None else round(prep_ms, 3),
     }
     # the same calls captured once in a HIP graph and replayed (no host launch cost per call):
