@@ -566,19 +566,21 @@ int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t* bytes)
     if (!bytes) return fail(DA_ERR_INVALID_ARG, "null bytes%s");
     if (k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
     if (k > 0x7ffffffeLL || nnz > 0x7fffffffLL) return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
-    *bytes = plan_transpose(k, (nnz + unit - 1) / unit).bytes;
+    *bytes = plan_transpose(k + 1, (nnz + unit - 1) / unit).bytes;        // sort keys lie in [0, k]
     return DA_OK;
 }
 
-int da_eb_schedule(int64_t k, int64_t nnz, const int32_t* colind, int unit, int32_t* order,
-                   void* workspace, size_t workspace_bytes, void* stream)
+int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
+                   int32_t* order, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
-    if (k > 0x7ffffffeLL || nnz > 0x7fffffffLL) return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
+    if (m < 0 || k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
+    if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
+        return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
     if (nnz == 0) return DA_OK;
-    if (!colind || !order) return fail(DA_ERR_INVALID_ARG, "null colind or order%s");
+    if (m == 0) return fail(DA_ERR_INVALID_ARG, "stored entries in a matrix without rows%s");
+    if (!rowptr || !colind || !order) return fail(DA_ERR_INVALID_ARG, "null rowptr, colind or order%s");
     const int64_t nunits = (nnz + unit - 1) / unit;
-    const TransposePlan t = plan_transpose(k, nunits);
+    const TransposePlan t = plan_transpose(k + 1, nunits);
     if (!workspace || workspace_bytes < t.bytes)
         return fail(DA_ERR_INVALID_ARG, "workspace missing or smaller than da_eb_schedule_workspace reports%s");
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
@@ -591,8 +593,12 @@ int da_eb_schedule(int64_t k, int64_t nnz, const int32_t* colind, int unit, int3
     int* hist = reinterpret_cast<int*>(ws + t.off_hist);
     int* part = reinterpret_cast<int*>(ws + t.off_part);
     const int n = (int)nunits;
-    hipLaunchKernelGGL(schedule_keys_kernel, dim3((unsigned)((n + kSortBlock - 1) / kSortBlock)), dim3(kSortBlock), 0, s,
-                       colind, unit, n, keys[0], ids[0], pad[0]);
+    const dim3 kgrid((unsigned)((n + kSortBlock - 1) / kSortBlock));
+    int* count = part;                                  // free until the first scan
+    hipLaunchKernelGGL(schedule_clear_kernel, dim3(1), dim3(1), 0, s, count);
+    hipLaunchKernelGGL(schedule_flags_kernel, kgrid, dim3(kSortBlock), 0, s, (int)m, (int)nnz, rowptr, colind, unit, n,
+                       keys[0], ids[0], pad[0], count);
+    hipLaunchKernelGGL(schedule_keys_kernel, kgrid, dim3(kSortBlock), 0, s, (int)k, n, keys[0], count);
     const int mask = (1 << t.digit_bits) - 1;
     for (int p = 0; p < t.passes; ++p) {
         const int shift = p * t.digit_bits;
@@ -641,7 +647,7 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
     for (int i = 0; i < 4; ++i) {
         pl.units[i] = (int)((nnz + kPlanUnits[i] - 1) / kPlanUnits[i]);
         ints += (size_t)((pl.units[i] + 63) & ~63);
-        const size_t b = plan_transpose(k, pl.units[i]).bytes;
+        const size_t b = plan_transpose(k + 1, pl.units[i]).bytes;
         ws_bytes = b > ws_bytes ? b : ws_bytes;
     }
     void* ws = nullptr;
@@ -654,7 +660,7 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
     for (int i = 0; i < 4 && status == DA_OK; ++i) {
         pl.order[i] = static_cast<int*>(pl.block) + off;
         off += (size_t)((pl.units[i] + 63) & ~63);
-        status = da_eb_schedule(k, nnz, colind, kPlanUnits[i], pl.order[i], ws, ws_bytes, stream);
+        status = da_eb_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], ws, ws_bytes, stream);
     }
     e = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(ws);

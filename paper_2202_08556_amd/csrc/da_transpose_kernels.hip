@@ -285,18 +285,48 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
     }
 }
 
-// Sort keys of the EB schedule: unit u (the stored entries [u*unit, (u+1)*unit)) is keyed by the
-// column index of its first entry; ids = 0, 1, 2, ...; pad = 0 (the value slot of the triples the
-// radix passes move is not used here).
-__global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(const int* __restrict__ colind, int unit, int nunits,
-                                                                   int* __restrict__ keys, int* __restrict__ ids,
-                                                                   float* __restrict__ pad)
+// Sort keys of the EB schedule for unit u (the stored entries [u*unit, (u+1)*unit)).
+// A unit inside one row covers a narrow column range and is keyed by the middle of that range,
+// 1 + (first + last column index)/2: these units are swept over B in column order.  A unit that
+// touches several rows spans the whole column range and no order helps it; where it goes depends on
+// how many such units there are:
+//   at least a quarter of all units:  key 0 -- they come first, in storage order, so that the sweep
+//       of the single-row units afterwards has the L2 to itself;
+//   fewer:  key 1 + u*k/nunits -- spread evenly through the sweep in storage order (a few
+//       latency-bound units among many bandwidth-bound ones cost nothing; bunched together at the
+//       start they leave the memory system idle).
+// schedule_flags_kernel marks the multi-row units (key -1) and counts them; schedule_keys_kernel
+// then fixes their keys.  ids = 0, 1, 2, ...; pad = 0 (the value slot of the triples the radix
+// passes move is not used).
+__global__ void schedule_clear_kernel(int* __restrict__ count) { *count = 0; }
+
+__global__ __launch_bounds__(kSortBlock) void schedule_flags_kernel(int m, int nnz, const int* __restrict__ rowptr,
+                                                                    const int* __restrict__ colind, int unit, int nunits,
+                                                                    int* __restrict__ keys, int* __restrict__ ids,
+                                                                    float* __restrict__ pad, int* __restrict__ count)
 {
     const long u = (long)blockIdx.x * kSortBlock + threadIdx.x;
-    if (u >= nunits) return;
-    keys[u] = colind[u * unit];
-    ids[u] = (int)u;
-    pad[u] = 0.f;
+    bool several = false;
+    if (u < nunits) {
+        const long c0 = u * unit;
+        const long c1 = min(c0 + unit, (long)nnz) - 1;
+        const int r0 = owner_row(rowptr, 0, m - 1, (int)c0);
+        several = rowptr[r0 + 1] <= c1;
+        keys[u] = several ? -1 : 1 + (int)(((long)colind[c0] + (long)colind[c1]) >> 1);
+        ids[u] = (int)u;
+        pad[u] = 0.f;
+    }
+    const unsigned long long vote = __ballot(several);
+    if ((threadIdx.x & 63) == 0 && vote) atomicAdd(count, __popcll(vote));
+}
+
+__global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int k, int nunits, int* __restrict__ keys,
+                                                                   const int* __restrict__ count)
+{
+    const long u = (long)blockIdx.x * kSortBlock + threadIdx.x;
+    if (u >= nunits || keys[u] >= 0) return;
+    const bool first = 4L * *count >= nunits;
+    keys[u] = first ? 0 : 1 + (int)(u * k / nunits);
 }
 
 // t_rowptr[c] = number of stored entries with column index < c, for c = 0..k.

@@ -187,6 +187,7 @@ def test_eb_schedule_matches_oracle(a, units):
     from paper_2202_08556_amd import binding as da
     dev = torch.device("cuda:0")
     ci = torch.from_numpy(a.colind).to(dev)
+    rp = torch.from_numpy(a.rowptr).to(dev)
     nnz = int(a.colind.size)
     for unit in units:
         print(f"schedule case {a.name} unit={unit}", flush=True)
@@ -194,11 +195,12 @@ def test_eb_schedule_matches_oracle(a, units):
         order = torch.full((nunits,), -3, dtype=torch.int32, device=dev)
         nbytes = da.da_eb_schedule_workspace(a.k, nnz, unit)
         ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        da.da_eb_schedule(a.k, nnz, ci, unit, order, ws, nbytes)
+        da.da_eb_schedule(a.m, a.k, nnz, rp, ci, unit, order, ws, nbytes)
         torch.cuda.synchronize()
-        assert np.array_equal(order.cpu().numpy(), orc.eb_schedule(a.colind, unit))
-    assert da.da_eb_schedule_status(a.k, nnz, ci, 64, order, ws, 8) == da.DA_ERR_INVALID_ARG
-    assert da.da_eb_schedule_status(a.k, nnz, ci, 0, order, ws, nbytes) == da.DA_ERR_INVALID_ARG
+        assert np.array_equal(order.cpu().numpy(), orc.eb_schedule(a.rowptr, a.colind, unit, a.k))
+    assert da.da_eb_schedule_status(a.m, a.k, nnz, rp, ci, 64, order, ws, 8) == da.DA_ERR_INVALID_ARG
+    assert da.da_eb_schedule_status(a.m, a.k, nnz, rp, ci, 0, order, ws, nbytes) == da.DA_ERR_INVALID_ARG
+    assert da.da_eb_schedule_status(a.m, a.k, nnz, None, ci, 64, order, ws, nbytes) == da.DA_ERR_INVALID_ARG
 
 
 PREPARED = [("skewed", lambda: gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001), [8, 64]),

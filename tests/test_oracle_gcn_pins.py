@@ -159,13 +159,27 @@ def test_gcn_layer_forward_and_gradients():
             assert abs(fd - grad[idx]) < 1e-6 * max(1.0, abs(grad[idx]))
 
 
-# T7 -- the chunk order: a permutation, keys ascending, ties by chunk number; against Python's
-#       tuple sort ---------------------------------------------------------------------------
-@pytest.mark.parametrize("unit", [1, 4, 7, 64])
-def test_eb_schedule_is_sorted_permutation(unit):
-    a = gen.skewed_csr(m=400, k=300, heavy_frac=0.02, heavy_lo=100, heavy_hi=250, seed=45)
-    order = orc.eb_schedule(a.colind, unit)
-    nunits = -(-a.colind.size // unit)
+# T7 -- the chunk order: a permutation sorted by key with ties by chunk number, against Python's
+#       tuple sort over keys derived from per-entry row numbers; both regimes of the multi-row
+#       chunks (many: first, in storage order; few: spread by storage position) -----------------------
+@pytest.mark.parametrize("unit,light_mean", [(1, 3.0), (4, 3.0), (7, 0.05), (64, 3.0), (16, 0.05)])
+def test_eb_schedule_is_sorted_permutation(unit, light_mean):
+    a = gen.skewed_csr(m=400, k=300, heavy_frac=0.05, heavy_lo=150, heavy_hi=290, light_mean=light_mean, seed=45)
+    order = orc.eb_schedule(a.rowptr, a.colind, unit, a.k)
+    nnz = a.colind.size
+    nunits = -(-nnz // unit)
     assert sorted(order.tolist()) == list(range(nunits))
-    expect = [c for _, c in sorted((int(a.colind[c * unit]), c) for c in range(nunits))]
-    assert order.tolist() == expect
+    row_of = np.repeat(np.arange(a.m), np.diff(a.rowptr))
+    several = [len(set(row_of[c * unit:min((c + 1) * unit, nnz)].tolist())) > 1 for c in range(nunits)]
+    many = 4 * sum(several) >= nunits
+    keyed = []
+    for c in range(nunits):
+        first, last = c * unit, min((c + 1) * unit, nnz) - 1
+        if several[c]:
+            keyed.append((0 if many else 1 + c * a.k // nunits, c))
+        else:
+            keyed.append((1 + (int(a.colind[first]) + int(a.colind[last])) // 2, c))
+    assert order.tolist() == [c for _, c in sorted(keyed)]
+    if unit >= 16:
+        assert any(several) and not all(several)
+        assert many == (light_mean > 1.0)                     # the two cases cover both regimes
