@@ -121,6 +121,13 @@ std::mutex g_plan_mu;
 Plan g_plans[16];
 int g_plan_next = 0;
 
+bool has_plan(const void* rowptr, const void* colind, int64_t m) {
+    std::lock_guard<std::mutex> lk(g_plan_mu);
+    for (const auto& pl : g_plans)
+        if (pl.block && pl.rowptr == rowptr && pl.colind == colind && pl.m == m) return true;
+    return false;
+}
+
 Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int chunk) {
     std::lock_guard<std::mutex> lk(g_plan_mu);
     for (const auto& pl : g_plans)
@@ -135,7 +142,7 @@ Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int 
 // column per lane.  Setting DA_SPMM_TUNE=1 lets DA_SPMM_V / _G / _NV / _CHUNK override the choice
 // (for tuning runs only; invalid combinations are rejected).
 int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const void* C, const Strides& sd,
-                  int64_t known_nnz, Geometry* out) {
+                  int64_t known_nnz, bool prepared, Geometry* out) {
     const uintptr_t addr = reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C);
     // 16-byte accesses need unit column strides and rows that start on 16-byte boundaries
     const bool vec4_ok = (N % 4 == 0) && (addr % 16 == 0) && sd.cb == 1 && sd.cc == 1 &&
@@ -169,7 +176,9 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
     }
     if (eb) {
         if (pr) g.chunk = kEntriesPerWavePR;
-        else g.chunk = g.G >= 8 ? 256 : (g.G == 4 ? 128 : 64);
+        // with a chunk schedule (prepared matrix) groups of 8 lanes do better on half-size chunks:
+        // twice as many waves pass through the machine and the sweep has a time axis
+        else g.chunk = g.G >= 16 ? 256 : (g.G == 8 ? (prepared ? 128 : 256) : (g.G == 4 ? 128 : 64));
         if (known_nnz >= 0) {
             // Small matrices: shrink the chunks until there are about four waves of workers per
             // SIMD, so that the chunk walk, a chain of dependent memory round trips, does not set
@@ -434,7 +443,8 @@ int da_spmm_ex(int64_t m, int64_t k, int64_t N, const int32_t* rowptr, const int
     const bool cm = (algo & 2) != 0;
     const bool pr = (algo & 1) != 0;
     Geometry g;
-    const int st = pick_geometry(cm, pr, eb, N, B, C, sd, eb ? lookup_nnz(rowptr, m) : -1, &g);
+    const int st = pick_geometry(cm, pr, eb, N, B, C, sd, eb ? lookup_nnz(rowptr, m) : -1,
+                                 eb && has_plan(rowptr, colind, m), &g);
     if (st != DA_OK) return st;
     const Family fam = eb ? (pr ? EB_PR : EB_SR) : (pr ? RB_PR : RB_SR);
     return dispatch(fam, g, p);
