@@ -150,20 +150,24 @@ int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, 
  * Not to be called while a da_spmm call on the same matrix is still executing (release likewise).
  *
  * da_eb_schedule is the building block: order[u], u = 0 .. ceil(nnz/unit)-1, lists the chunk
- * numbers (chunk c = stored entries [c*unit, (c+1)*unit)) sorted by a key, ties in ascending chunk
- * number -- deterministic.  A chunk inside one row covers a narrow column range and has the key
- * 1 + (colind[first entry] + colind[last entry])/2: these chunks are swept over B in column order.
- * A chunk that touches several rows spans the whole column range whatever its place; it gets key 0
- * (first, in storage order) when at least a quarter of all chunks are of that kind, and key
- * 1 + c*k/nunits (spread evenly among the others) when they are few.  Caller workspace as for
- * da_csr_transpose (size from da_eb_schedule_workspace, 256-byte aligned); enqueues only.
+ * numbers (chunk c = stored entries [c*unit, (c+1)*unit)) sorted by a key in [0, 2k), ties in
+ * ascending chunk number -- deterministic.  A chunk inside one row covers a narrow column range
+ * and has the key k + (colind[first entry] + colind[last entry])/2: these chunks are swept over B
+ * in column order.  A chunk that touches several rows is keyed by the column index of its first
+ * entry: colind[first] when at least a quarter of all chunks are of that kind (they then form a
+ * first segment of the schedule, before the sweep), k + colind[first] when they are few (mixed
+ * into the sweep).  *first_segment (device, may be NULL) receives the number of chunks of that
+ * first segment, 0 when there is none.  k <= 2^30 (DA_ERR_UNSUPPORTED beyond; da_spmm_prepare then
+ * builds no order).  Caller workspace as for da_csr_transpose (size from
+ * da_eb_schedule_workspace, 256-byte aligned); enqueues only.
  */
 int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t *rowptr, const int32_t *colind,
                     void *stream);
 int da_spmm_release(const int32_t *rowptr);
 int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t *bytes /* host, out */);
 int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t *rowptr, const int32_t *colind,
-                   int unit, int32_t *order, void *workspace, size_t workspace_bytes, void *stream);
+                   int unit, int32_t *order, int32_t *first_segment,
+                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Debug aid: check on the device that the CSR arrays are well formed -- rowptr[0] == 0, rowptr

@@ -13,7 +13,7 @@ Contents (each cites the passage of the paper it follows):
                           pass of the aggregation step of a graph-convolution layer (Sec. 6, GCN)
   csr_transpose           CSR arrays of A^T with ascending indices inside every row
   gcn_layer / gcn_layer_backward   relu(A.(X.W) + b) and its gradients in fp64 (Sec. 6, GCN)
-  eb_schedule             order in which EB workers take their chunks (multi-row chunks, then column sweep)
+  eb_schedule             order in which EB workers take their chunks (column sweep; multi-row chunks apart)
   features                input characteristics of Sec. 5.1, Table 2 (nnz, matrix size, standard
                           deviation of row lengths, N) plus mean / max row length
   conditional_reduction   the conditional prefix-sum network of Sec. 4 (EB+RM+PR, Fig. 6(e)),
@@ -214,12 +214,13 @@ def gcn_layer_backward(rowptr, colind, vals, X, W, Z, d_out, relu: bool = True):
 
 
 def eb_schedule(rowptr, colind, unit: int, k: int):
-    """Chunk numbers 0 .. ceil(nnz/unit)-1 of the element-balanced partition (Sec. 3.2: a worker owns
-    `unit` consecutive stored entries) in the order in which the workers take them: ascending key,
-    ties by chunk number.  A chunk inside one row has key 1 + (first + last column index) // 2 (the
-    middle of the column range it covers).  A chunk that touches several rows has key 0 when at
-    least a quarter of all chunks are of that kind (they then come first, in storage order) and
-    key 1 + c*k // nunits otherwise (spread evenly, in storage order, among the others).  Any
+    """(order, first_segment): chunk numbers 0 .. ceil(nnz/unit)-1 of the element-balanced partition
+    (Sec. 3.2: a worker owns `unit` consecutive stored entries) in the order in which the workers
+    take them -- ascending key, ties by chunk number -- and the number of chunks of the first
+    segment.  A chunk inside one row has key k + (first + last column index) // 2 (the middle of the
+    column range it covers).  A chunk that touches several rows is keyed by its first column index:
+    as it is when at least a quarter of all chunks are of that kind (they then come first and form
+    the first segment), plus k otherwise (mixed among the others; first_segment = 0).  Any
     permutation gives the same product; this one makes concurrently running workers touch
     neighbouring rows of the dense operand."""
     rowptr = np.asarray(rowptr, dtype=np.int64)
@@ -232,13 +233,15 @@ def eb_schedule(rowptr, colind, unit: int, k: int):
         first, last = c * unit, min((c + 1) * unit, nnz) - 1
         row_first = int(np.searchsorted(rowptr, first, side="right")) - 1     # last row starting at or before `first`
         if last < rowptr[row_first + 1]:
-            keys[c] = 1 + (colind[first] + colind[last]) // 2
+            keys[c] = k + (colind[first] + colind[last]) // 2
         else:
             several[c] = True
-    if 4 * int(several.sum()) < nunits:
-        idx = np.nonzero(several)[0]
-        keys[idx] = 1 + idx * k // nunits
-    return np.argsort(keys, kind="stable").astype(np.int32)
+            keys[c] = colind[first]
+    first_segment = int(several.sum())
+    if 4 * first_segment < nunits:
+        keys[several] += k
+        first_segment = 0
+    return np.argsort(keys, kind="stable").astype(np.int32), first_segment
 
 
 # --------------------------------------------------------------------------------------------

@@ -55,7 +55,7 @@ _lib.da_spmm_release.argtypes = [_vp]
 _lib.da_spmm_release.restype = ctypes.c_int
 _lib.da_eb_schedule_workspace.argtypes = [_i64, _i64, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
 _lib.da_eb_schedule_workspace.restype = ctypes.c_int
-_lib.da_eb_schedule.argtypes = [_i64, _i64, _i64, _vp, _vp, ctypes.c_int, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.da_eb_schedule.argtypes = [_i64, _i64, _i64, _vp, _vp, ctypes.c_int, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.da_eb_schedule.restype = ctypes.c_int
 _lib.da_spmm_algo_name.argtypes = [ctypes.c_int]
 _lib.da_spmm_algo_name.restype = ctypes.c_char_p
@@ -222,13 +222,16 @@ def da_eb_schedule_workspace(k, nnz, unit) -> int:
     return int(out.value)
 
 
-def da_eb_schedule_status(m, k, nnz, rowptr, colind, unit, order, workspace, workspace_bytes, stream=None) -> int:
+def da_eb_schedule_status(m, k, nnz, rowptr, colind, unit, order, first_segment, workspace, workspace_bytes,
+                          stream=None) -> int:
     return int(_lib.da_eb_schedule(int(m), int(k), int(nnz), _ptr(rowptr), _ptr(colind), int(unit), _ptr(order),
-                                   _ptr(workspace), int(workspace_bytes), _stream(stream)))
+                                   _ptr(first_segment), _ptr(workspace), int(workspace_bytes), _stream(stream)))
 
 
-def da_eb_schedule(m, k, nnz, rowptr, colind, unit, order, workspace, workspace_bytes, stream=None) -> None:
-    _check(da_eb_schedule_status(m, k, nnz, rowptr, colind, unit, order, workspace, workspace_bytes, stream))
+def da_eb_schedule(m, k, nnz, rowptr, colind, unit, order, first_segment, workspace, workspace_bytes,
+                   stream=None) -> None:
+    _check(da_eb_schedule_status(m, k, nnz, rowptr, colind, unit, order, first_segment, workspace, workspace_bytes,
+                                 stream))
 
 
 def da_spmm_algo_name(algo: int):

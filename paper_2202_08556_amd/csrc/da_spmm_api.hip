@@ -115,6 +115,7 @@ struct Plan {
     int64_t m, nnz;
     int* order[4];
     int units[4];
+    int first_units[4];   // chunks of the first schedule segment (multi-row chunks, when they go first)
     void* block;
 };
 std::mutex g_plan_mu;
@@ -128,13 +129,16 @@ bool has_plan(const void* rowptr, const void* colind, int64_t m) {
     return false;
 }
 
+// Schedule of a prepared matrix for this chunk size; split holds the CHUNKS of the first segment
+// here, the launch turns it into blocks.
 Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int chunk) {
     std::lock_guard<std::mutex> lk(g_plan_mu);
     for (const auto& pl : g_plans)
         if (pl.block && pl.rowptr == rowptr && pl.colind == colind && pl.m == m)
             for (int i = 0; i < 4; ++i)
-                if (kPlanUnits[i] == chunk) return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0};
-    return Schedule{nullptr, 0, 0, 0};
+                if (kPlanUnits[i] == chunk)
+                    return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0, pl.first_units[i], 0, 0, 0};
+    return Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0};
 }
 
 // Default geometry per algorithm family and N.  Measured on MI355X: 16-byte and 4-byte gathers
@@ -252,21 +256,34 @@ int launch_w(Family fam, const Problem& p, const Geometry& geo) {
         const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
         hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.C, chunk);
         // chunk order of a prepared matrix (column sweep), if one exists for this chunk size
-        Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0) ? Schedule{nullptr, 0, 0, 0}
+        Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0) ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0}
                                                          : lookup_schedule(p.rowptr, p.colind, p.m, chunk);
-        if (sch.order && !pin) {
-            // deal the schedule to the XCDs in stripes (sweep_block)
-            // stripe length near geo.stripe such that whole rounds of 8 stripes cover the blocks with
-            // next to no surplus (all XCDs then get the same number of stripes)
+        const int first_chunks = sch.split;
+        sch.split = 0;
+        if (sch.order && !pin && geo.stripe > 0) {
+            // Deal the schedule to the XCDs in stripes (sweep_block).  Stripe length near geo.stripe
+            // such that whole rounds of 8 stripes cover a segment with next to no surplus (all XCDs
+            // then get the same number of stripes).  When the schedule starts with a segment of
+            // multi-row chunks, that segment and the rest are dealt separately: the two kinds of
+            // chunk cost differently, and every XCD should get the same share of both.
             const long wpb = fam == EB_SR ? (long)kWavesPerBlock * (kWave / G) : (long)kWavesPerBlock;
             const long nvb = (sch.units + wpb - 1) / wpb;
-            const long per_xcd = (nvb + 7) / 8;
-            if (geo.stripe > 0 && per_xcd >= 2) {
+            auto deal = [&](long nb, int* stripe_out) {        // blocks per XCD, rounded up to whole stripes
+                const long per_xcd = (nb + 7) / 8;
                 long rounds = (per_xcd + geo.stripe / 2) / geo.stripe;
                 if (rounds < 1) rounds = 1;
-                sch.stripe = (int)((per_xcd + rounds - 1) / rounds);
-                const long covered = 8L * sch.stripe * rounds;
-                if (blocks >= nvb) blocks = covered;       // one chunk per worker
+                *stripe_out = (int)((per_xcd + rounds - 1) / rounds);
+                return (long)*stripe_out * rounds;
+            };
+            long split = env_int("DA_SPMM_NO_SPLIT", 0) ? 0 : first_chunks / wpb;
+            if (split < 16 || nvb - split < 16) split = 0;
+            if (nvb >= 16) {
+                long per_b = 0;
+                sch.split = (int)split;
+                sch.per_a = (int)deal(split > 0 ? split : nvb, &sch.stripe);
+                if (split > 0) per_b = deal(nvb - split, &sch.stripe_b); else sch.stripe_b = 1;
+                sch.vblocks = (int)(8 * (sch.per_a + per_b));
+                if (blocks >= nvb) blocks = sch.vblocks;      // one chunk per worker
             }
             blocks = (blocks + 7) / 8 * 8;                 // block b stays on XCD b % 8 on every pass
         }
@@ -576,21 +593,23 @@ int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t* bytes)
     if (!bytes) return fail(DA_ERR_INVALID_ARG, "null bytes%s");
     if (k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
     if (k > 0x7ffffffeLL || nnz > 0x7fffffffLL) return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
-    *bytes = plan_transpose(k + 1, (nnz + unit - 1) / unit).bytes;        // sort keys lie in [0, k]
+    if (k > (1LL << 30)) return fail(DA_ERR_UNSUPPORTED, "more than 2^30 columns%s");
+    *bytes = plan_transpose(2 * k, (nnz + unit - 1) / unit).bytes;        // sort keys lie in [0, 2k)
     return DA_OK;
 }
 
 int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
-                   int32_t* order, void* workspace, size_t workspace_bytes, void* stream)
+                   int32_t* order, int32_t* first_segment, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (m < 0 || k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
     if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
         return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
+    if (k > (1LL << 30)) return fail(DA_ERR_UNSUPPORTED, "more than 2^30 columns%s");
     if (nnz == 0) return DA_OK;
     if (m == 0) return fail(DA_ERR_INVALID_ARG, "stored entries in a matrix without rows%s");
     if (!rowptr || !colind || !order) return fail(DA_ERR_INVALID_ARG, "null rowptr, colind or order%s");
     const int64_t nunits = (nnz + unit - 1) / unit;
-    const TransposePlan t = plan_transpose(k + 1, nunits);
+    const TransposePlan t = plan_transpose(2 * k, nunits);
     if (!workspace || workspace_bytes < t.bytes)
         return fail(DA_ERR_INVALID_ARG, "workspace missing or smaller than da_eb_schedule_workspace reports%s");
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
@@ -606,9 +625,9 @@ int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, con
     const dim3 kgrid((unsigned)((n + kSortBlock - 1) / kSortBlock));
     int* count = part;                                  // free until the first scan
     hipLaunchKernelGGL(schedule_clear_kernel, dim3(1), dim3(1), 0, s, count);
-    hipLaunchKernelGGL(schedule_flags_kernel, kgrid, dim3(kSortBlock), 0, s, (int)m, (int)nnz, rowptr, colind, unit, n,
-                       keys[0], ids[0], pad[0], count);
-    hipLaunchKernelGGL(schedule_keys_kernel, kgrid, dim3(kSortBlock), 0, s, (int)k, n, keys[0], count);
+    hipLaunchKernelGGL(schedule_flags_kernel, kgrid, dim3(kSortBlock), 0, s, (int)m, (int)k, (int)nnz, rowptr, colind,
+                       unit, n, keys[0], ids[0], pad[0], count);
+    hipLaunchKernelGGL(schedule_keys_kernel, kgrid, dim3(kSortBlock), 0, s, (int)k, n, keys[0], count, first_segment);
     const int mask = (1 << t.digit_bits) - 1;
     for (int p = 0; p < t.passes; ++p) {
         const int shift = p * t.digit_bits;
@@ -651,13 +670,14 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
         const int v = da_csr_validate(m, k, nnz, rowptr, colind, stream);
         if (v != DA_OK) return v;
     }
+    if (k > (1LL << 30)) { remember_nnz(rowptr, m, nnz); return DA_OK; }    // no schedule for such widths
     Plan pl{};
     pl.rowptr = rowptr; pl.colind = colind; pl.m = m; pl.nnz = nnz;
-    size_t ints = 0, ws_bytes = 0;
+    size_t ints = 64, ws_bytes = 0;                        // the first 4 ints receive the segment sizes
     for (int i = 0; i < 4; ++i) {
         pl.units[i] = (int)((nnz + kPlanUnits[i] - 1) / kPlanUnits[i]);
         ints += (size_t)((pl.units[i] + 63) & ~63);
-        const size_t b = plan_transpose(k + 1, pl.units[i]).bytes;
+        const size_t b = plan_transpose(2 * k, pl.units[i]).bytes;
         ws_bytes = b > ws_bytes ? b : ws_bytes;
     }
     void* ws = nullptr;
@@ -666,13 +686,17 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
     e = hipMalloc(&ws, ws_bytes);
     if (e != hipSuccess) { (void)hipFree(pl.block); return hip_fail(e, "hipMalloc"); }
     int status = DA_OK;
-    size_t off = 0;
+    size_t off = 64;
+    int* seg = static_cast<int*>(pl.block);
     for (int i = 0; i < 4 && status == DA_OK; ++i) {
         pl.order[i] = static_cast<int*>(pl.block) + off;
         off += (size_t)((pl.units[i] + 63) & ~63);
-        status = da_eb_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], ws, ws_bytes, stream);
+        status = da_eb_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], seg + i, ws, ws_bytes, stream);
     }
-    e = hipStreamSynchronize((hipStream_t)stream);
+    e = hipSuccess;
+    if (status == DA_OK)
+        e = hipMemcpyAsync(pl.first_units, seg, sizeof pl.first_units, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(ws);
     if (status == DA_OK && e != hipSuccess) status = hip_fail(e, "da_spmm_prepare");
     if (status != DA_OK) { (void)hipFree(pl.block); return status; }

@@ -44,15 +44,18 @@ struct Strides {
 // instead of chunk u.  The order is a permutation of 0..units-1 built for a matrix with `nnz`
 // stored entries and the chunk size of the launch; a kernel that finds another nnz on the device
 // ignores it (order == nullptr: no schedule).
-// stripe > 0: the schedule is dealt to the 8 XCDs in stripes of `stripe` blocks (see sweep_block).
-// The kernel rounds the number of blocks up to whole rounds of 8 stripes (surplus blocks find no
-// chunk), so the host picks a stripe length that makes this surplus small; the grid's x extent must
-// be a multiple of 8 so that a block stays on its XCD when it makes more than one pass.
+// stripe > 0: the schedule is dealt to the 8 XCDs in stripes (see sweep_block).  The schedule may
+// consist of two segments that are dealt separately, blocks [0, split) in stripes of `stripe`
+// blocks and the rest in stripes of `stripe_b`, so that every XCD gets the same share of both
+// (split == 0: one segment).  per_a = blocks of the first segment per XCD, rounded up to whole
+// stripes; vblocks = number of block positions to walk (8 * blocks per XCD over both segments;
+// positions that fall outside a segment find no chunk).  The grid's x extent must be a multiple of
+// 8 so that a block stays on its XCD when it makes more than one pass.
 struct Schedule {
     const int* order;
     int units;
     int nnz;
-    int stripe;
+    int stripe, split, per_a, stripe_b, vblocks;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -289,13 +292,20 @@ __device__ __forceinline__ BlockMap block_map(int pin_tiles) {
 
 // Position in the schedule of (virtual) block vb when the schedule is swept by all XCDs together:
 // workgroups go round-robin to the 8 XCDs, so block vb runs on XCD vb % 8 and is that XCD's
-// (vb / 8)-th block.  Stripe t of XCD x is stripe 8 t + x of the schedule: at any time the XCDs work
+// (vb / 8)-th block.  Stripe t of XCD x is stripe 8 t + x of the segment: at any time the XCDs work
 // on 8 neighbouring stripes, each on its own, and the rows of B that one L2 has to hold are an
-// eighth of the band all running workers cover.  A bijection on [0, n) for n a multiple of 8*stripe.
-__device__ __forceinline__ long sweep_block(long vb, int stripe) {
-    const unsigned x = (unsigned)vb & 7u, l = (unsigned)(vb >> 3), st = (unsigned)stripe;   // block counts fit 32 bits
-    const unsigned t = l / st;
-    return (long)(t * 8u + x) * st + (l - t * st);
+// eighth of the band all running workers cover.  Returns -1 for a position outside its segment.
+__device__ __forceinline__ long sweep_block(long vb, const Schedule& sch) {
+    const unsigned x = (unsigned)vb & 7u;                 // block counts fit 32 bits
+    unsigned l = (unsigned)(vb >> 3);
+    if (l < (unsigned)sch.per_a) {
+        const unsigned st = (unsigned)sch.stripe, t = l / st;
+        const long sb = (long)(t * 8u + x) * st + (l - t * st);
+        return (sch.split > 0 && sb >= sch.split) ? -1 : sb;
+    }
+    l -= (unsigned)sch.per_a;
+    const unsigned st = (unsigned)sch.stripe_b, t = l / st;
+    return sch.split + (long)(t * 8u + x) * st + (l - t * st);
 }
 
 // Calls f(Count<UU>, t) for t covering [0, cnt) in blocks of UMAX, then 4, 2, 1 entries, so that
@@ -536,16 +546,13 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
 
     const long nunits = ((unsigned)nnz + (unsigned)chunk - 1u) / (unsigned)chunk;   // nnz < 2^31
     const bool scheduled = sch.order != nullptr && sch.nnz == nnz && sch.units == nunits;
-    const int stripe = (scheduled && pin_tiles <= 0) ? sch.stripe : 0;
+    const bool striped = scheduled && pin_tiles <= 0 && sch.stripe > 0;
     constexpr long WPB = kWavesPerBlock * GPW;            // workers per block
-    long nvb = (nunits + WPB - 1) / WPB;                  // blocks needed to cover every chunk once
-    if (stripe > 0) {                                     // whole rounds of 8 stripes
-        const unsigned round = 8u * (unsigned)stripe;
-        nvb = (long)(((unsigned)nvb + round - 1) / round) * round;
-    }
+    const long nvb = striped ? sch.vblocks : (nunits + WPB - 1) / WPB;   // block positions to walk
     for (long vb = bm.bx; vb < nvb; vb += bm.nbx) {
-        const long u = (stripe > 0 ? sweep_block(vb, stripe) : vb) * WPB + wave * GPW + g;
-        if (u >= nunits) continue;
+        const long sb = striped ? sweep_block(vb, sch) : vb;
+        const long u = sb * WPB + wave * GPW + g;
+        if (sb < 0 || u >= nunits) continue;
         const long c0l = (scheduled ? (long)sch.order[u] : u) * chunk;
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);
@@ -662,15 +669,12 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
 
     const long nunits = ((unsigned)nnz + (unsigned)chunk - 1u) / (unsigned)chunk;   // nnz < 2^31
     const bool scheduled = sch.order != nullptr && sch.nnz == nnz && sch.units == nunits;
-    const int stripe = (scheduled && pin_tiles <= 0) ? sch.stripe : 0;
-    long nvb = (nunits + kWavesPerBlock - 1) / kWavesPerBlock;   // blocks needed to cover every chunk once
-    if (stripe > 0) {                                     // whole rounds of 8 stripes
-        const unsigned round = 8u * (unsigned)stripe;
-        nvb = (long)(((unsigned)nvb + round - 1) / round) * round;
-    }
+    const bool striped = scheduled && pin_tiles <= 0 && sch.stripe > 0;
+    const long nvb = striped ? sch.vblocks : (nunits + kWavesPerBlock - 1) / kWavesPerBlock;   // block positions to walk
     for (long vb = bm.bx; vb < nvb; vb += bm.nbx) {
-        const long u = (stripe > 0 ? sweep_block(vb, stripe) : vb) * kWavesPerBlock + wave;
-        if (u >= nunits) continue;
+        const long sb = striped ? sweep_block(vb, sch) : vb;
+        const long u = sb * kWavesPerBlock + wave;
+        if (sb < 0 || u >= nunits) continue;
         const long c0l = (scheduled ? (long)sch.order[u] : u) * chunk;
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);

@@ -285,22 +285,23 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
     }
 }
 
-// Sort keys of the EB schedule for unit u (the stored entries [u*unit, (u+1)*unit)).
+// Sort keys of the EB schedule for unit u (the stored entries [u*unit, (u+1)*unit)), in [0, 2k).
 // A unit inside one row covers a narrow column range and is keyed by the middle of that range,
-// 1 + (first + last column index)/2: these units are swept over B in column order.  A unit that
-// touches several rows spans the whole column range and no order helps it; where it goes depends on
-// how many such units there are:
-//   at least a quarter of all units:  key 0 -- they come first, in storage order, so that the sweep
-//       of the single-row units afterwards has the L2 to itself;
-//   fewer:  key 1 + u*k/nunits -- spread evenly through the sweep in storage order (a few
-//       latency-bound units among many bandwidth-bound ones cost nothing; bunched together at the
-//       start they leave the memory system idle).
-// schedule_flags_kernel marks the multi-row units (key -1) and counts them; schedule_keys_kernel
-// then fixes their keys.  ids = 0, 1, 2, ...; pad = 0 (the value slot of the triples the radix
-// passes move is not used).
+// k + (first + last column index)/2: these units are swept over B in column order.  A unit that
+// touches several rows is keyed by its first column index (units that start at the same place of
+// rows of similar length walk the column range in step, so this aligns them too; for units of many
+// short rows no order matters):
+//   at least a quarter of all units are of that kind:  key = first column -- they form a first
+//       segment of the schedule, so that the sweep of the single-row units has the L2 to itself;
+//   fewer:  key = k + first column -- they are mixed into the sweep (a few latency-bound units
+//       among many bandwidth-bound ones cost nothing; bunched together they leave the memory
+//       system idle).
+// schedule_flags_kernel marks the multi-row units (negative key) and counts them;
+// schedule_keys_kernel then fixes their keys and publishes the size of the first segment.
+// ids = 0, 1, 2, ...; pad = 0 (the value slot of the triples the radix passes move is not used).
 __global__ void schedule_clear_kernel(int* __restrict__ count) { *count = 0; }
 
-__global__ __launch_bounds__(kSortBlock) void schedule_flags_kernel(int m, int nnz, const int* __restrict__ rowptr,
+__global__ __launch_bounds__(kSortBlock) void schedule_flags_kernel(int m, int k, int nnz, const int* __restrict__ rowptr,
                                                                     const int* __restrict__ colind, int unit, int nunits,
                                                                     int* __restrict__ keys, int* __restrict__ ids,
                                                                     float* __restrict__ pad, int* __restrict__ count)
@@ -312,7 +313,7 @@ __global__ __launch_bounds__(kSortBlock) void schedule_flags_kernel(int m, int n
         const long c1 = min(c0 + unit, (long)nnz) - 1;
         const int r0 = owner_row(rowptr, 0, m - 1, (int)c0);
         several = rowptr[r0 + 1] <= c1;
-        keys[u] = several ? -1 : 1 + (int)(((long)colind[c0] + (long)colind[c1]) >> 1);
+        keys[u] = several ? -1 - colind[c0] : k + (int)(((long)colind[c0] + (long)colind[c1]) >> 1);
         ids[u] = (int)u;
         pad[u] = 0.f;
     }
@@ -320,13 +321,18 @@ __global__ __launch_bounds__(kSortBlock) void schedule_flags_kernel(int m, int n
     if ((threadIdx.x & 63) == 0 && vote) atomicAdd(count, __popcll(vote));
 }
 
+// first_segment (may be null) receives the number of units of the first segment: the count of
+// multi-row units when they go first, else 0.
 __global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int k, int nunits, int* __restrict__ keys,
-                                                                   const int* __restrict__ count)
+                                                                   const int* __restrict__ count,
+                                                                   int* __restrict__ first_segment)
 {
     const long u = (long)blockIdx.x * kSortBlock + threadIdx.x;
-    if (u >= nunits || keys[u] >= 0) return;
     const bool first = 4L * *count >= nunits;
-    keys[u] = first ? 0 : 1 + (int)(u * k / nunits);
+    if (u == 0 && first_segment) *first_segment = first ? *count : 0;
+    if (u >= nunits || keys[u] >= 0) return;
+    const int col = -1 - keys[u];
+    keys[u] = first ? col : k + col;
 }
 
 // t_rowptr[c] = number of stored entries with column index < c, for c = 0..k.

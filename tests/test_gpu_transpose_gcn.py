@@ -193,14 +193,20 @@ def test_eb_schedule_matches_oracle(a, units):
         print(f"schedule case {a.name} unit={unit}", flush=True)
         nunits = -(-nnz // unit)
         order = torch.full((nunits,), -3, dtype=torch.int32, device=dev)
+        seg = torch.full((1,), -3, dtype=torch.int32, device=dev)
         nbytes = da.da_eb_schedule_workspace(a.k, nnz, unit)
         ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        da.da_eb_schedule(a.m, a.k, nnz, rp, ci, unit, order, ws, nbytes)
+        da.da_eb_schedule(a.m, a.k, nnz, rp, ci, unit, order, seg, ws, nbytes)
         torch.cuda.synchronize()
-        assert np.array_equal(order.cpu().numpy(), orc.eb_schedule(a.rowptr, a.colind, unit, a.k))
-    assert da.da_eb_schedule_status(a.m, a.k, nnz, rp, ci, 64, order, ws, 8) == da.DA_ERR_INVALID_ARG
-    assert da.da_eb_schedule_status(a.m, a.k, nnz, rp, ci, 0, order, ws, nbytes) == da.DA_ERR_INVALID_ARG
-    assert da.da_eb_schedule_status(a.m, a.k, nnz, None, ci, 64, order, ws, nbytes) == da.DA_ERR_INVALID_ARG
+        ref_order, ref_seg = orc.eb_schedule(a.rowptr, a.colind, unit, a.k)
+        assert np.array_equal(order.cpu().numpy(), ref_order)
+        assert int(seg.item()) == ref_seg
+        da.da_eb_schedule(a.m, a.k, nnz, rp, ci, unit, order, None, ws, nbytes)      # the count is optional
+        torch.cuda.synchronize()
+        assert np.array_equal(order.cpu().numpy(), ref_order)
+    assert da.da_eb_schedule_status(a.m, a.k, nnz, rp, ci, 64, order, None, ws, 8) == da.DA_ERR_INVALID_ARG
+    assert da.da_eb_schedule_status(a.m, a.k, nnz, rp, ci, 0, order, None, ws, nbytes) == da.DA_ERR_INVALID_ARG
+    assert da.da_eb_schedule_status(a.m, a.k, nnz, None, ci, 64, order, None, ws, nbytes) == da.DA_ERR_INVALID_ARG
 
 
 PREPARED = [("skewed", lambda: gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001), [8, 64]),

@@ -161,11 +161,11 @@ def test_gcn_layer_forward_and_gradients():
 
 # T7 -- the chunk order: a permutation sorted by key with ties by chunk number, against Python's
 #       tuple sort over keys derived from per-entry row numbers; both regimes of the multi-row
-#       chunks (many: first, in storage order; few: spread by storage position) -----------------------
+#       chunks (many: a first segment; few: mixed into the sweep) ---------------------------------
 @pytest.mark.parametrize("unit,light_mean", [(1, 3.0), (4, 3.0), (7, 0.05), (64, 3.0), (16, 0.05)])
 def test_eb_schedule_is_sorted_permutation(unit, light_mean):
     a = gen.skewed_csr(m=400, k=300, heavy_frac=0.05, heavy_lo=150, heavy_hi=290, light_mean=light_mean, seed=45)
-    order = orc.eb_schedule(a.rowptr, a.colind, unit, a.k)
+    order, first_segment = orc.eb_schedule(a.rowptr, a.colind, unit, a.k)
     nnz = a.colind.size
     nunits = -(-nnz // unit)
     assert sorted(order.tolist()) == list(range(nunits))
@@ -176,10 +176,13 @@ def test_eb_schedule_is_sorted_permutation(unit, light_mean):
     for c in range(nunits):
         first, last = c * unit, min((c + 1) * unit, nnz) - 1
         if several[c]:
-            keyed.append((0 if many else 1 + c * a.k // nunits, c))
+            keyed.append((int(a.colind[first]) + (0 if many else a.k), c))
         else:
-            keyed.append((1 + (int(a.colind[first]) + int(a.colind[last])) // 2, c))
+            keyed.append((a.k + (int(a.colind[first]) + int(a.colind[last])) // 2, c))
     assert order.tolist() == [c for _, c in sorted(keyed)]
+    assert first_segment == (sum(several) if many else 0)
+    if many:                                                  # the first segment is exactly the multi-row chunks
+        assert sorted(order[:first_segment].tolist()) == [c for c in range(nunits) if several[c]]
     if unit >= 16:
         assert any(several) and not all(several)
         assert many == (light_mean > 1.0)                     # the two cases cover both regimes
