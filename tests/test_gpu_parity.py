@@ -204,17 +204,21 @@ print("overrides ok")
     assert res.returncode == 0 and "overrides ok" in res.stdout, res.stdout + res.stderr
 
 
-def test_calls_can_be_captured_in_a_hip_graph(gpu):
+@pytest.mark.parametrize("prepared", [False, True], ids=["plain", "prepared"])
+def test_calls_can_be_captured_in_a_hip_graph(gpu, prepared):
     """da_spmm only enqueues kernels (no allocation, no synchronisation, no memset nodes), so a
     sequence of calls can be captured once and replayed; every replay must reproduce the eager
-    result, with eager work and synchronisations between the replays."""
+    result, with eager work and synchronisations between the replays.  Also with a prepared matrix
+    large enough for the chunk schedule and its XCD stripes to be in use."""
     from paper_2202_08556_amd import binding as da
-    a = gen.uniform_csr(seed=1000)
+    a = gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001) if prepared else gen.uniform_csr(seed=1000)
     N = 8
     B = gen.dense(a.k, N, "uniform", seed=1000)
     c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
     prob = gpu(a, B)
     da.da_spmm_features(a.m, N, prob.rowptr)
+    if prepared:
+        da.da_spmm_prepare(a.m, a.k, a.nnz, prob.rowptr, prob.colind)
     dev = prob.B.device
     outs = [torch.full((a.m, N), float("nan"), device=dev) for _ in range(8)]
     side = torch.cuda.Stream()
@@ -236,6 +240,8 @@ def test_calls_can_be_captured_in_a_hip_graph(gpu):
         for algo in ALGOS:
             r = orc.tolerance_ratio(outs[algo].cpu().numpy(), c_ref, s_abs)
             assert r <= 1.0, f"replay {replay} algo {algo}: {r}"
+    if prepared:
+        da.da_spmm_release(prob.rowptr)
 
 
 @pytest.mark.parametrize("b_col,c_col", [(False, False), (True, False), (False, True), (True, True)])
