@@ -64,3 +64,47 @@ def test_largest_index_range_bit_exact():
             assert orc.bit_mismatches(C[rows_dev].cpu().numpy(), c_ref) == 0, (prepared, algo)
             assert bool(torch.isfinite(C).all())
     da.da_spmm_release(rowptr)
+
+
+def test_operands_beyond_4_gib_take_the_wide_kernels():
+    """B and C of 8 GiB each (2^21 x 1024 floats): element offsets exceed 32 bits, so the library must
+    use its 64-bit gather addressing by itself.  Integer data, bit-exact on sampled rows; the oracle
+    gets the sampled rows with their columns renumbered onto a compact copy of the B rows they use."""
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    m = k = 1 << 21
+    N, per_row = 1024, 3
+    rows_all = torch.arange(m, dtype=torch.int64, device=dev)
+    rowptr = (torch.arange(m + 1, dtype=torch.int64, device=dev) * per_row).to(torch.int32)
+    t = torch.arange(per_row, dtype=torch.int64, device=dev)
+    colind = ((rows_all[:, None] * 977 + t[None, :] * 699053 + 5) % k).reshape(-1).to(torch.int32)
+    vals = (((rows_all[:, None] + t[None, :]) % 3) + 1).reshape(-1).to(torch.float32)
+    nnz = m * per_row
+
+    def b_values(r, n):                                   # closed form, same on host and device
+        return ((r * 31 + n * 17) % 9) - 4
+
+    B = torch.empty((k, N), dtype=torch.float32, device=dev)
+    ncol = torch.arange(N, dtype=torch.int64, device=dev)
+    for r0 in range(0, k, 1 << 17):
+        r = torch.arange(r0, min(k, r0 + (1 << 17)), dtype=torch.int64, device=dev)
+        B[r0:r0 + r.shape[0]] = b_values(r[:, None], ncol[None, :]).to(torch.float32)
+    C = torch.empty((m, N), dtype=torch.float32, device=dev)
+    assert B.numel() * 4 > (1 << 32)
+    rng = np.random.default_rng(8)
+    rows = np.unique(np.concatenate([rng.integers(0, m, size=1500), [0, m - 1]])).astype(np.int64)
+    idx = (torch.from_numpy(rows).to(dev)[:, None] * per_row + t[None, :]).reshape(-1)
+    sub_cols = colind[idx].cpu().numpy().astype(np.int64)
+    used, compact = np.unique(sub_cols, return_inverse=True)
+    B_small = b_values(used[:, None], np.arange(N, dtype=np.int64)[None, :]).astype(np.float32)
+    sub_rowptr = (np.arange(rows.size + 1, dtype=np.int64) * per_row).astype(np.int32)
+    c_ref, _ = orc.spmm(sub_rowptr, compact.astype(np.int32), vals[idx].cpu().numpy(), B_small, want_abs=False)
+    da.da_spmm_features(m, N, rowptr)
+    rows_dev = torch.from_numpy(rows).to(dev)
+    for algo in range(8):
+        print(f"beyond-4-GiB case algo={algo}", flush=True)
+        C.fill_(float("nan"))
+        da.da_spmm(m, k, N, rowptr, colind, vals, B, C, algo)
+        torch.cuda.synchronize()
+        assert orc.bit_mismatches(C[rows_dev].cpu().numpy(), c_ref) == 0, algo
+        assert bool(torch.isfinite(C[-4096:]).all()) and bool(torch.isfinite(C[:4096]).all())
