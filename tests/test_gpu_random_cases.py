@@ -1,6 +1,8 @@
 """Seeded random small cases through the C ABI against the oracle: shapes, row-length laws, N,
 storage orders and leading dimensions drawn at random, every algorithm id, with and without the
 per-matrix preparation.  The sizes keep the oracle at milliseconds per case."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -31,7 +33,8 @@ def draw_case(seed):
     return a, N, rng
 
 
-@pytest.mark.parametrize("seed", list(range(9000, 9040)))
+# DA_TEST_RANDOM_CASES=n widens the default 40 seeds for an occasional longer run
+@pytest.mark.parametrize("seed", list(range(9000, 9000 + int(os.environ.get("DA_TEST_RANDOM_CASES", "40")))))
 def test_random_case(seed):
     from paper_2202_08556_amd import binding as da
     a, N, rng = draw_case(seed)
@@ -64,3 +67,46 @@ def test_random_case(seed):
     finally:
         if prepared:
             da.da_spmm_release(rp)
+
+
+def draw_medium_case(seed):
+    rng = np.random.default_rng(seed)
+    m = int(rng.integers(20000, 200000))
+    kind = int(rng.integers(0, 3))
+    if kind == 0:
+        a = gen.lognormal_csr(m, float(rng.uniform(8.0, 300.0)), float(rng.choice([0.0, 0.3, 2.0, 8.0])), seed=seed,
+                              name="lognormal")
+    elif kind == 1:
+        a = gen.skewed_csr(m=m, heavy_frac=float(rng.uniform(0.0005, 0.01)), heavy_lo=2000, heavy_hi=min(m, 40000),
+                           light_mean=float(rng.uniform(0.5, 20.0)), seed=seed)
+    else:
+        a = gen.powerlaw_csr(m=m, scale=float(rng.uniform(3.0, 12.0)), max_len=int(rng.choice([512, 4096])), seed=seed)
+    return a, int(rng.choice([8, 32, 64, 128])), rng
+
+
+@pytest.mark.parametrize("seed", list(range(9500, 9510)))
+def test_random_medium_case_prepared(seed):
+    """Matrices large enough for the chunk schedule, its two segments and the XCD stripes to be in
+    use (a few hundred thousand to a few million entries): every id on a prepared matrix against the
+    oracle on sampled rows plus the longest rows."""
+    from paper_2202_08556_amd import binding as da
+    a, N, rng = draw_medium_case(seed)
+    print(f"random medium case seed={seed} {a.name} m={a.m} nnz={a.nnz} N={N}", flush=True)
+    dev = torch.device("cuda:0")
+    B = gen.dense(a.k, N, "uniform", seed=seed + 1)
+    rows = np.unique(np.concatenate([rng.integers(0, a.m, size=1500), np.argsort(a.row_lengths())[-32:],
+                                     [0, a.m - 1]])).astype(np.int64)
+    c_ref, s_abs = orc.spmm_rows(rows, a.rowptr, a.colind, a.vals, B)
+    rp, ci, va, Bd = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals, B))
+    da.da_spmm_features(a.m, N, rp)
+    da.da_spmm_prepare(a.m, a.k, a.nnz, rp, ci)
+    try:
+        for algo in range(8):
+            C = torch.full((a.m, N), float("nan"), device=dev)
+            da.da_spmm(a.m, a.k, N, rp, ci, va, Bd, C, algo)
+            torch.cuda.synchronize()
+            c = C.cpu().numpy()
+            assert np.isfinite(c).all(), (seed, algo)
+            assert orc.tolerance_ratio(c[rows], c_ref, s_abs) <= 1.0, (seed, algo)
+    finally:
+        da.da_spmm_release(rp)
