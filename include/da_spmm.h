@@ -22,6 +22,7 @@
  * Environment switches (read at every call; for debugging and measurement, not for production)
  *   DA_SPMM_DEBUG_VALIDATE=1   check the CSR arrays on the device before every product / transpose
  *   DA_SPMM_NO_SCHEDULE=1      ignore the chunk orders of prepared matrices (da_spmm_prepare)
+ *   DA_SPMM_NO_SPLIT=1         deal such an order to the XCDs as one segment instead of two
  *   DA_SPMM_WIDE=1             force the kernels with 64-bit gather addresses
  *   DA_SPMM_TUNE=1             honour DA_SPMM_V / _G / _NV / _CHUNK / _PIN / _STRIPE, which override the
  *                              launch geometry; unsupported combinations return DA_ERR_UNSUPPORTED
