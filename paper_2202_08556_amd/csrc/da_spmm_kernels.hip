@@ -607,7 +607,15 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
                             acc.clear();
                             shared_with_prev = false;
                             if (next < c1) {
-                                do { ++row; row_end = rowptr[row + 1]; } while (row_end <= next);
+                                // the next row with entries: usually row + 1; after a few rows
+                                // without entries search instead of walking (a run of thousands
+                                // of empty rows would otherwise cost a dependent load each)
+                                int walked = 0;
+                                do { ++row; row_end = rowptr[row + 1]; } while (row_end <= next && ++walked < 4);
+                                if (row_end <= next) {
+                                    row = row_of_entry_group<G>(rowptr, row + 1, m - 1, next, j, g * G);
+                                    row_end = rowptr[row + 1];
+                                }
                             }
                         }
                     }

@@ -14,6 +14,19 @@ pytestmark = pytest.mark.gpu
 ALGOS = list(range(8))
 
 
+def hypersparse(m=120000, k=4000, seed=31):
+    """Most rows empty, in runs from one to hundreds of rows, between short rows: a chunk of stored
+    entries then spans many rows with long gaps (the EB row walk has to skip the runs)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    lens = np.zeros(m, np.int64)
+    pos = np.cumsum(rng.choice([1, 2, 3, 5, 9, 40, 300], size=m))      # gaps of every kind
+    pos = pos[pos < m]
+    lens[pos] = rng.integers(1, 30, size=len(pos))
+    rowptr, colind = gen.csr_from_lens(rng, lens, k)
+    vals = rng.uniform(-1.0, 1.0, size=len(colind)).astype(np.float32)
+    return gen.CSR(m, k, rowptr.astype(np.int32), colind.astype(np.int32), vals, "hypersparse", seed)
+
+
 def problems():
     """Sizes the oracle finishes in well under a second each, spanning several tiles and chunks,
     with ragged tails in m, nnz and N."""
@@ -28,6 +41,7 @@ def problems():
     yield "one_long_row", gen.skewed_csr(m=64, k=40000, heavy_frac=0.02, heavy_lo=30000,
                                          heavy_hi=30000, light_mean=0.5, seed=9), [8, 12]
     yield "rmat", gen.rmat_csr(12, 16.0, 0.57, 0.19, 0.19, seed=8102), [4, 32]
+    yield "hypersparse", hypersparse(), [8, 64, 128]
     # wide B: several column tiles with a ragged last one (520 = 2*256 + 8; 1030 is not a multiple of 4)
     yield "wide_N", gen.skewed_csr(m=900, k=700, heavy_frac=0.01, heavy_lo=300, heavy_hi=600, seed=10), [520, 1030]
 
