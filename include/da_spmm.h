@@ -155,7 +155,10 @@ int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, 
  * like da_spmm_features does.  A kernel that finds another nnz on the device than the plan was
  * built for ignores the plan, so a stale plan costs speed, never correctness; the contents of
  * colind may change freely.  Allocates and frees temporary device memory, synchronises `stream`.
- * Not to be called while a da_spmm call on the same matrix is still executing (release likewise).
+ * Prepare, release and the product calls may be issued from several host threads: a plan is freed
+ * only after the kernels already launched with it have finished (the free waits for the device).
+ * A HIP graph captured from an EB call on a prepared matrix holds the address of the plan's order:
+ * keep the plan (no release, no re-prepare, fewer than 16 later prepares) while the graph is replayed.
  *
  * da_eb_schedule is the building block: order[u], u = 0 .. ceil(nnz/unit)-1, lists the chunk
  * numbers (chunk c = stored entries [c*unit, (c+1)*unit)) sorted by a key in [0, 2k), ties in

@@ -130,9 +130,10 @@ bool has_plan(const void* rowptr, const void* colind, int64_t m) {
 }
 
 // Schedule of a prepared matrix for this chunk size; split holds the CHUNKS of the first segment
-// here, the launch turns it into blocks.
-Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int chunk) {
-    std::lock_guard<std::mutex> lk(g_plan_mu);
+// here, the launch turns it into blocks.  The caller holds g_plan_mu from this lookup until the
+// kernel that reads the order has been launched: plans are freed only under that mutex, and hipFree
+// waits for work already launched, so the order cannot disappear under a kernel.
+Schedule lookup_schedule_locked(const void* rowptr, const void* colind, int64_t m, int chunk) {
     for (const auto& pl : g_plans)
         if (pl.block && pl.rowptr == rowptr && pl.colind == colind && pl.m == m)
             for (int i = 0; i < 4; ++i)
@@ -256,8 +257,9 @@ int launch_w(Family fam, const Problem& p, const Geometry& geo) {
         const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
         hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.C, chunk);
         // chunk order of a prepared matrix (column sweep), if one exists for this chunk size
+        std::lock_guard<std::mutex> plan_lock(g_plan_mu);
         Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0) ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0}
-                                                         : lookup_schedule(p.rowptr, p.colind, p.m, chunk);
+                                                         : lookup_schedule_locked(p.rowptr, p.colind, p.m, chunk);
         const int first_chunks = sch.split;
         sch.split = 0;
         if (sch.order && !pin && geo.stripe > 0) {

@@ -351,3 +351,49 @@ def test_wide_address_kernels_match_oracle(gpu, monkeypatch):
         for algo in ALGOS:
             print(f"wide case {a.name} N={N} algo={algo}", flush=True)
             assert orc.tolerance_ratio(prob.run(algo), c_ref, s_abs) <= 1.0, (a.name, N, algo)
+
+
+def test_concurrent_host_threads_on_their_own_streams(gpu):
+    """Four host threads call the library at once, each on its own stream and matrix (one of them
+    preparing and releasing its matrix between calls): every result matches the oracle."""
+    import threading
+    from paper_2202_08556_amd import binding as da
+    dev = torch.device("cuda:0")
+    jobs = []
+    for t, (a, N) in enumerate([(gen.lognormal_csr(6000, 30.0, 3.0, seed=90), 32),
+                                (gen.powerlaw_csr(m=8192, seed=91), 128),
+                                (gen.uniform_csr(m=5000, k=3000, mean_len=9, seed=92), 8),
+                                (gen.skewed_csr(m=8192, heavy_lo=2000, heavy_hi=6000, seed=93), 64)]):
+        Bh = gen.dense(a.k, N, "uniform", seed=94 + t)
+        c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, Bh)
+        rp, ci, va, Bd = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals, Bh))
+        jobs.append(dict(a=a, N=N, rp=rp, ci=ci, va=va, B=Bd, C=torch.empty((a.m, N), device=dev),
+                         ref=c_ref, s_abs=s_abs, stream=torch.cuda.Stream(), worst=0.0, error=None))
+    torch.cuda.synchronize()
+
+    def work(t, job):
+        try:
+            a, N = job["a"], job["N"]
+            for it in range(24):
+                algo = (it + t) % 8
+                if t % 2 == 0 and it % 6 == 0:
+                    da.da_spmm_prepare(a.m, a.k, a.nnz, job["rp"], job["ci"], stream=job["stream"])
+                if t % 2 == 0 and it % 6 == 5:
+                    da.da_spmm_release(job["rp"])
+                da.da_spmm(a.m, a.k, N, job["rp"], job["ci"], job["va"], job["B"], job["C"], algo,
+                           stream=job["stream"])
+                job["stream"].synchronize()
+                c = job["C"].cpu().numpy()
+                job["worst"] = max(job["worst"], orc.tolerance_ratio(c, job["ref"], job["s_abs"]))
+        except Exception as e:                      # reported by the main thread
+            job["error"] = repr(e)
+
+    threads = [threading.Thread(target=work, args=(t, job)) for t, job in enumerate(jobs)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    for job in jobs:
+        da.da_spmm_release(job["rp"])
+        assert job["error"] is None, job["error"]
+        assert job["worst"] <= 1.0
