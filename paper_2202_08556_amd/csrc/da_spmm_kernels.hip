@@ -488,7 +488,8 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 // must start from zero; a row without entries is touched by no worker.  This pass zeroes exactly
 // those two kinds of rows so that C needs no full memset.  `chunk` is the number of entries per
 // worker of the product kernel that follows.  A wave inspects 64 rows (one per lane) and then
-// clears the flagged ones together, one row at a time, with full-width stores.
+// clears the flagged ones together: one row at a time with full-width stores when a row takes
+// more than 32 stores, several rows per store instruction otherwise.
 // ------------------------------------------------------------------------------------------
 template <int V>
 __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
@@ -507,11 +508,28 @@ __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
     float z[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) z[v] = 0.f;
-    while (mask) {
-        const int r = __ffsll((long long)mask) - 1;
-        mask &= mask - 1;
-        float* __restrict__ crow = C + (base + r) * sd.rc;
-        for (int n0 = lane * V; n0 < N; n0 += kWave * V) store_vec<V>(crow + (long)n0 * sd.cc, z);
+    const int vecs = (N + V - 1) / V;                     // stores per row
+    if (vecs > kWave / 2) {
+        while (mask) {
+            const int r = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            float* __restrict__ crow = C + (base + r) * sd.rc;
+            for (int n0 = lane * V; n0 < N; n0 += kWave * V) store_vec<V>(crow + (long)n0 * sd.cc, z);
+        }
+    } else {
+        // short rows of C: T lanes per row, 64/T flagged rows per store instruction.  The flagged
+        // lanes list themselves in LDS in lane order; lane group s then takes list entries
+        // s, s + 64/T, ...
+        __shared__ unsigned char listed[kWavesPerBlock][kWave];
+        const int count = __popcll(mask);
+        if (need) listed[wave][__popcll(mask & ((1ull << lane) - 1ull))] = (unsigned char)lane;
+        wave_lds_sync();
+        const int T = vecs <= 1 ? 1 : 1 << (32 - __clz(vecs - 1));   // power of two >= vecs, <= 32
+        const int n0 = (lane & (T - 1)) * V;
+        for (int s = lane / T; s < count; s += kWave / T) {
+            const int r = listed[wave][s];
+            if (n0 < N) store_vec<V>(C + (base + r) * sd.rc + (long)n0 * sd.cc, z);
+        }
     }
 }
 

@@ -14,6 +14,7 @@ families below stand in for it and span the input dynamics the paper names as de
   powerlaw_csr   graph-like: heavy-tailed row lengths, popularity-skewed columns
   stencil27_csr  3-D 27-point stencil: very regular rows, banded columns
   skewed_csr     almost all rows tiny, a handful of enormous rows
+  hypersparse_csr  nearly all rows empty, stored rows separated by long runs of empty ones
   sweep_csr      one member j of a 64-matrix family spanning size / density / dispersion
   fig6a_csr      the 5-row 6/2/0/3/1 structure the paper uses to explain its techniques
                  (Sec. 4, Fig. 6(a)); values and columns are not printed there, so they
@@ -27,8 +28,8 @@ import numpy as np
 
 __all__ = [
     "CSR", "uniform_csr", "powerlaw_csr", "stencil27_csr", "skewed_csr", "sweep_csr",
-    "sweep_params", "fig6a_csr", "lognormal_csr", "rmat_csr", "csr_from_lens", "dense", "dense_int",
-    "integer_twin", "config_seed",
+    "sweep_params", "fig6a_csr", "lognormal_csr", "rmat_csr", "reversed_edges", "hypersparse_csr",
+    "csr_from_lens", "dense", "dense_int", "integer_twin", "config_seed",
 ]
 
 
@@ -252,6 +253,20 @@ def skewed_csr(m: int = 524288, k: int | None = None, heavy_frac: float = 1e-3,
 # ----------------------------------------------------------------------------------------------
 # config 5: selector sweep family
 # ----------------------------------------------------------------------------------------------
+def hypersparse_csr(m: int, k: int | None = None, row_frac: float = 0.01, mean_len: float = 100.0,
+                    seed: int = 4500) -> CSR:
+    """Only round(row_frac*m) rows, at seeded positions, hold entries (length 1 + Poisson(mean_len - 1),
+    clipped to k); all other rows are empty, so stored rows are separated by long runs of empty
+    ones.  Uniform distinct sorted columns, values U(-1,1)."""
+    k = m if k is None else k
+    rng = _rng(seed)
+    lens = np.zeros(m, dtype=np.int64)
+    rows = rng.choice(m, size=max(1, int(round(row_frac * m))), replace=False)
+    lens[rows] = np.minimum(1 + rng.poisson(max(mean_len - 1.0, 0.0), size=rows.size), k)
+    rowptr, colind = csr_from_lens(rng, lens, k)
+    return CSR(m, k, rowptr, colind, _uniform_vals(rng, colind.size), "hypersparse", seed)
+
+
 def lognormal_csr(m: int, mean_len: float, cv: float, seed: int, k: int | None = None,
                   name: str = "lognormal") -> CSR:
     """Row lengths = clip(round(LogNormal(mu, sigma^2)), 0, k) with sigma^2 = ln(1+cv^2),

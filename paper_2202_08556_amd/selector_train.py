@@ -2,7 +2,8 @@
 
     python -m paper_2202_08556_amd.selector_train \
         --train paper_2202_08556_amd/selector_data/train.jsonl paper_2202_08556_amd/selector_data/families.jsonl \
-        --eval paper_2202_08556_amd/selector_data/eval.jsonl
+        --eval paper_2202_08556_amd/selector_data/eval.jsonl \
+        --also-score paper_2202_08556_amd/selector_data/odd.jsonl
 
 The paper trains a gradient-boosted tree classifier (LightGBM) on `nnz, mat_size, std_row, N`
 (Table 2).  LightGBM is not available here, so the model is a small gradient-boosted forest built
@@ -145,6 +146,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--train", nargs="+", required=True)
     ap.add_argument("--eval", nargs="+", required=True)
+    ap.add_argument("--also-score", nargs="*", default=[],
+                    help="further never-trained-on sets, scored with the shipped model and reported one by one")
     ap.add_argument("--trees", type=int, default=120)
     ap.add_argument("--depth", type=int, default=5)
     ap.add_argument("--report", default=os.path.join(PKG, "selector_data", "report.txt"))
@@ -167,6 +170,9 @@ def main():
     model = fit(Xtr[perm[nv:]], Ttr[perm[nv:]], Xtr[perm[:nv]], Ttr[perm[:nv]], n_trees=args.trees, depth=args.depth)
     report("evaluation sweep (64 matrices x 6 N, disjoint seeds from training)", Tev, predict(model, Xev), lines)
     report("training sets (resubstitution)", Ttr, predict(model, Xtr), lines)
+    for p in args.also_score:
+        Xo, To, _ = load([p])
+        report(f"{os.path.basename(p)} (never trained on)", To, predict(model, Xo), lines)
     # (c) feature ablation with the paper's protocol: its own four features (Table 2) against the
     #     extended set compiled into the library.  Columns of the feature vector: 0 log2 rows,
     #     1 log2 nnz, 2 log2(mean+1), 3 std/mean, 4 log2(max+1), 5 log2 N, 6 log2(max/mean+1).

@@ -4,13 +4,16 @@ scored on (paper Sec. 5: every design is run on every matrix, the model learns w
     python -m paper_2202_08556_amd.sweep --set eval  --members 0-63  --out results/sweep_eval.jsonl
     python -m paper_2202_08556_amd.sweep --set train --members 0-255 --out results/sweep_train.jsonl
     python -m paper_2202_08556_amd.sweep --set families --out results/sweep_families.jsonl
+    python -m paper_2202_08556_amd.sweep --set odd --out results/sweep_odd.jsonl
 
 Sets
   eval      the 64-member selector sweep (seed base 5000), never trained on
   train     members of the same lognormal family with a disjoint seed base (100000) and a lower
             size cap (2^24 entries), used for training only
   families  scaled versions of the uniform / power-law / stencil / skewed workloads with seeds
-            disjoint from the benchmark configurations, used for training only
+            disjoint from the benchmark configurations, plus odd shapes (see odd_members), used
+            for training only
+  odd       other members of those odd shapes (different sizes and seeds), never trained on
 
 One JSON line per (matrix, N): features as returned by da_spmm_features, and the time of each id
 in microseconds (HIP events around a batch of back-to-back calls that rotate over 3 copies of B
@@ -67,6 +70,40 @@ def family_members():
                                            (16, 32.0, 0.45, 0.15), (17, 8.0, 0.65, 0.15))):
         fam.append((f"rmat_s{scale}_e{int(ef)}_a{int(a * 100)}",
                     lambda scale=scale, ef=ef, a=a, b=b, i=i: gen.rmat_csr(scale, ef, a, b, b, seed=7500 + i)))
+    fam.extend(odd_members(7600, train=True))
+    return fam
+
+
+def odd_members(seed0: int, train: bool):
+    """Shapes far from the lognormal family: nearly all rows empty, about one entry per row, a few
+    very long rows in a wide matrix, millions of short rows over few columns, single dense rows.
+    The training members (train=True) and the evaluation members differ in sizes and seeds."""
+    if train:
+        hyper = ((1 << 20, 0.01, 100.0), (1 << 22, 0.001, 500.0), (1 << 21, 0.1, 8.0), (1 << 23, 0.0002, 4.0))
+        short = ((1 << 21, 1 << 21, 1.0), (1 << 22, 1 << 19, 0.5))
+        wide = ((2000, 1 << 22, 5000.0), (500, 1 << 20, 20000.0))
+        tall = ((6_000_000, 2000, 3.0), (2_000_000, 500, 6.0))
+        dense_rows = ((300_000, 1, 250_000, 8.0), (100_000, 5, 80_000, 2.0))
+    else:
+        hyper = ((3_000_000, 0.005, 60.0), (6_000_000, 0.0005, 300.0))
+        short = ((3_000_000, 3_000_000, 1.5),)
+        wide = ((1000, 2_000_000, 8000.0),)
+        tall = ((4_000_000, 1000, 4.0),)
+        dense_rows = ((200_000, 2, 150_000, 6.0),)
+    fam = []
+    for i, (m, frac, mean) in enumerate(hyper):
+        fam.append((f"hypersparse_m{m}_f{frac}", lambda m=m, frac=frac, mean=mean, i=i:
+                    gen.hypersparse_csr(m, m // 8, frac, mean, seed=seed0 + i)))
+    for i, (m, k, mean) in enumerate(short):
+        fam.append((f"short_m{m}_k{k}", lambda m=m, k=k, mean=mean, i=i: gen.uniform_csr(m, k, mean, seed=seed0 + 10 + i)))
+    for i, (m, k, mean) in enumerate(wide):
+        fam.append((f"wide_m{m}_k{k}", lambda m=m, k=k, mean=mean, i=i: gen.uniform_csr(m, k, mean, seed=seed0 + 20 + i)))
+    for i, (m, k, mean) in enumerate(tall):
+        fam.append((f"tall_m{m}_k{k}", lambda m=m, k=k, mean=mean, i=i: gen.uniform_csr(m, k, mean, seed=seed0 + 30 + i)))
+    for i, (m, rows, length, light) in enumerate(dense_rows):
+        fam.append((f"denserows_m{m}_r{rows}", lambda m=m, rows=rows, length=length, light=light, i=i:
+                    gen.skewed_csr(m=m, heavy_frac=rows / m, heavy_lo=length, heavy_hi=length, light_mean=light,
+                                   seed=seed0 + 40 + i)))
     return fam
 
 
@@ -130,7 +167,7 @@ def run_matrix(a, tag, member, setname, out, done, ns=NS):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--set", default="eval", choices=["eval", "train", "families"])
+    ap.add_argument("--set", default="eval", choices=["eval", "train", "families", "odd"])
     ap.add_argument("--members", default=None)
     ap.add_argument("--out", required=True)
     ap.add_argument("--max-seconds", type=float, default=1e9, help="stop starting new matrices after this")
@@ -145,8 +182,9 @@ def main():
                 pass
     t0 = time.time()
     with open(args.out, "a") as out:
-        if args.set == "families":
-            for idx, (name, make) in enumerate(family_members()):
+        if args.set in ("families", "odd"):
+            members = family_members() if args.set == "families" else odd_members(7800, train=False)
+            for idx, (name, make) in enumerate(members):
                 if all((args.set, name, N) in done for N in NS):
                     continue
                 if time.time() - t0 > args.max_seconds:

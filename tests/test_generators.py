@@ -136,3 +136,15 @@ def test_reversed_edges_is_the_same_edge_set_reversed():
         assert np.all(np.diff(seg) > 0)
     # popular columns become rows longer than any row of the original (capped at 256 entries)
     assert t.row_lengths().max() > 2 * a.row_lengths().max()
+
+
+def test_hypersparse_has_few_stored_rows_between_long_empty_runs():
+    a = gen.hypersparse_csr(200_000, 5000, row_frac=0.005, mean_len=40.0, seed=11)
+    check_structure(a)
+    lens = a.row_lengths()
+    stored = np.nonzero(lens)[0]
+    assert stored.size == 1000 and lens[stored].min() >= 1
+    assert 30 < lens[stored].mean() < 50
+    assert np.diff(stored).max() > 500                      # runs of hundreds of empty rows
+    again = gen.hypersparse_csr(200_000, 5000, row_frac=0.005, mean_len=40.0, seed=11)
+    assert np.array_equal(again.rowptr, a.rowptr) and np.array_equal(again.colind, a.colind)
