@@ -164,11 +164,11 @@ int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, 
  * numbers (chunk c = stored entries [c*unit, (c+1)*unit)) sorted by a key in [0, 2k), ties in
  * ascending chunk number -- deterministic.  A chunk inside one row covers a narrow column range
  * and has the key k + (colind[first entry] + colind[last entry])/2: these chunks are swept over B
- * in column order.  A chunk that touches several rows is keyed by the column index of its first
- * entry: colind[first] when at least a quarter of all chunks are of that kind (they then form a
- * first segment of the schedule, before the sweep), k + colind[first] when they are few (mixed
- * into the sweep).  *first_segment (device, may be NULL) receives the number of chunks of that
- * first segment, 0 when there is none.  k <= 2^30 (DA_ERR_UNSUPPORTED beyond; da_spmm_prepare then
+ * in column order.  A chunk that touches several rows has the key colind[first entry]: all such
+ * chunks sort before the others and form a first segment of the schedule (they are latency-bound
+ * where the others are bandwidth-bound, and a wave that holds both kinds runs at the pace of the
+ * slower).  *first_segment (device, may be NULL) receives the number of chunks of that first
+ * segment.  k <= 2^30 (DA_ERR_UNSUPPORTED beyond; da_spmm_prepare then
  * builds no order).  Caller workspace as for da_csr_transpose (size from
  * da_eb_schedule_workspace, 256-byte aligned); enqueues only.
  */

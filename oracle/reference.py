@@ -218,11 +218,10 @@ def eb_schedule(rowptr, colind, unit: int, k: int):
     (Sec. 3.2: a worker owns `unit` consecutive stored entries) in the order in which the workers
     take them -- ascending key, ties by chunk number -- and the number of chunks of the first
     segment.  A chunk inside one row has key k + (first + last column index) // 2 (the middle of the
-    column range it covers).  A chunk that touches several rows is keyed by its first column index:
-    as it is when at least a quarter of all chunks are of that kind (they then come first and form
-    the first segment), plus k otherwise (mixed among the others; first_segment = 0).  Any
-    permutation gives the same product; this one makes concurrently running workers touch
-    neighbouring rows of the dense operand."""
+    column range it covers).  A chunk that touches several rows is keyed by its first column index
+    alone: these chunks come first and form the first segment.  Any permutation gives the same
+    product; this one makes concurrently running workers touch neighbouring rows of the dense
+    operand and keeps the two kinds of chunk apart."""
     rowptr = np.asarray(rowptr, dtype=np.int64)
     colind = np.asarray(colind, dtype=np.int64)
     nnz = colind.size
@@ -237,11 +236,7 @@ def eb_schedule(rowptr, colind, unit: int, k: int):
         else:
             several[c] = True
             keys[c] = colind[first]
-    first_segment = int(several.sum())
-    if 4 * first_segment < nunits:
-        keys[several] += k
-        first_segment = 0
-    return np.argsort(keys, kind="stable").astype(np.int32), first_segment
+    return np.argsort(keys, kind="stable").astype(np.int32), int(several.sum())
 
 
 # --------------------------------------------------------------------------------------------

@@ -625,11 +625,10 @@ int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, con
     int* part = reinterpret_cast<int*>(ws + t.off_part);
     const int n = (int)nunits;
     const dim3 kgrid((unsigned)((n + kSortBlock - 1) / kSortBlock));
-    int* count = part;                                  // free until the first scan
+    int* count = first_segment ? first_segment : part;  // part is free until the first scan
     hipLaunchKernelGGL(schedule_clear_kernel, dim3(1), dim3(1), 0, s, count);
-    hipLaunchKernelGGL(schedule_flags_kernel, kgrid, dim3(kSortBlock), 0, s, (int)m, (int)k, (int)nnz, rowptr, colind,
+    hipLaunchKernelGGL(schedule_keys_kernel, kgrid, dim3(kSortBlock), 0, s, (int)m, (int)k, (int)nnz, rowptr, colind,
                        unit, n, keys[0], ids[0], pad[0], count);
-    hipLaunchKernelGGL(schedule_keys_kernel, kgrid, dim3(kSortBlock), 0, s, (int)k, n, keys[0], count, first_segment);
     const int mask = (1 << t.digit_bits) - 1;
     for (int p = 0; p < t.passes; ++p) {
         const int shift = p * t.digit_bits;

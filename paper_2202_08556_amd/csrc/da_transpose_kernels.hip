@@ -288,23 +288,20 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
 // Sort keys of the EB schedule for unit u (the stored entries [u*unit, (u+1)*unit)), in [0, 2k).
 // A unit inside one row covers a narrow column range and is keyed by the middle of that range,
 // k + (first + last column index)/2: these units are swept over B in column order.  A unit that
-// touches several rows is keyed by its first column index (units that start at the same place of
-// rows of similar length walk the column range in step, so this aligns them too; for units of many
-// short rows no order matters):
-//   at least a quarter of all units are of that kind:  key = first column -- they form a first
-//       segment of the schedule, so that the sweep of the single-row units has the L2 to itself;
-//   fewer:  key = k + first column -- they are mixed into the sweep (a few latency-bound units
-//       among many bandwidth-bound ones cost nothing; bunched together they leave the memory
-//       system idle).
-// schedule_flags_kernel marks the multi-row units (negative key) and counts them;
-// schedule_keys_kernel then fixes their keys and publishes the size of the first segment.
+// touches several rows is keyed by its first column index alone (units that start at the same
+// place of rows of similar length walk the column range in step, so this aligns them too; for
+// units of many short rows no order matters): all such units sort before the others and form a
+// first segment of the schedule.  They walk row ends (stores, atomics, a row-pointer load each) and
+// are latency-bound where the single-row units are bandwidth-bound; a wave that holds both kinds
+// runs at the pace of the slower, so the kinds are kept apart, and the launch deals each segment
+// to all XCDs.  count (one int, cleared first) receives the number of units of that segment.
 // ids = 0, 1, 2, ...; pad = 0 (the value slot of the triples the radix passes move is not used).
 __global__ void schedule_clear_kernel(int* __restrict__ count) { *count = 0; }
 
-__global__ __launch_bounds__(kSortBlock) void schedule_flags_kernel(int m, int k, int nnz, const int* __restrict__ rowptr,
-                                                                    const int* __restrict__ colind, int unit, int nunits,
-                                                                    int* __restrict__ keys, int* __restrict__ ids,
-                                                                    float* __restrict__ pad, int* __restrict__ count)
+__global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int m, int k, int nnz, const int* __restrict__ rowptr,
+                                                                   const int* __restrict__ colind, int unit, int nunits,
+                                                                   int* __restrict__ keys, int* __restrict__ ids,
+                                                                   float* __restrict__ pad, int* __restrict__ count)
 {
     const long u = (long)blockIdx.x * kSortBlock + threadIdx.x;
     bool several = false;
@@ -313,26 +310,12 @@ __global__ __launch_bounds__(kSortBlock) void schedule_flags_kernel(int m, int k
         const long c1 = min(c0 + unit, (long)nnz) - 1;
         const int r0 = owner_row(rowptr, 0, m - 1, (int)c0);
         several = rowptr[r0 + 1] <= c1;
-        keys[u] = several ? -1 - colind[c0] : k + (int)(((long)colind[c0] + (long)colind[c1]) >> 1);
+        keys[u] = several ? colind[c0] : k + (int)(((long)colind[c0] + (long)colind[c1]) >> 1);
         ids[u] = (int)u;
         pad[u] = 0.f;
     }
     const unsigned long long vote = __ballot(several);
     if ((threadIdx.x & 63) == 0 && vote) atomicAdd(count, __popcll(vote));
-}
-
-// first_segment (may be null) receives the number of units of the first segment: the count of
-// multi-row units when they go first, else 0.
-__global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int k, int nunits, int* __restrict__ keys,
-                                                                   const int* __restrict__ count,
-                                                                   int* __restrict__ first_segment)
-{
-    const long u = (long)blockIdx.x * kSortBlock + threadIdx.x;
-    const bool first = 4L * *count >= nunits;
-    if (u == 0 && first_segment) *first_segment = first ? *count : 0;
-    if (u >= nunits || keys[u] >= 0) return;
-    const int col = -1 - keys[u];
-    keys[u] = first ? col : k + col;
 }
 
 // t_rowptr[c] = number of stored entries with column index < c, for c = 0..k.
