@@ -101,6 +101,7 @@ def fit(X, T, Xval=None, Tval=None, n_trees=60, depth=5, lr=0.15, min_leaf=4, se
                 best_score, best_model = sc, model
     if Xval is None:
         return dict(trees=trees)
+    best_model["validation_score"] = best_score
     return best_model
 
 
@@ -148,8 +149,9 @@ def main():
     ap.add_argument("--eval", nargs="+", required=True)
     ap.add_argument("--also-score", nargs="*", default=[],
                     help="further never-trained-on sets, scored with the shipped model and reported one by one")
-    ap.add_argument("--trees", type=int, default=120)
-    ap.add_argument("--depth", type=int, default=5)
+    ap.add_argument("--trees", type=int, default=240)
+    ap.add_argument("--depth", type=int, nargs="+", default=[4, 5, 6],
+                    help="tree depths to try; the held-out tenth of the training sets picks one")
     ap.add_argument("--report", default=os.path.join(PKG, "selector_data", "report.txt"))
     ap.add_argument("--no-write", action="store_true")
     args = ap.parse_args()
@@ -161,13 +163,20 @@ def main():
     perm = np.random.RandomState(1).permutation(len(Xall))
     n4, n5 = int(0.4 * len(perm)), int(0.5 * len(perm))
     itr, iva, ite = perm[:n4], perm[n4:n5], perm[n5:]
-    m = fit(Xall[itr], Tall[itr], Xall[iva], Tall[iva], n_trees=args.trees, depth=args.depth)
+    def fit_best(X, T, Xv, Tv):
+        """One model per depth; the validation part picks the depth (and, inside fit, the number of trees)."""
+        models = [fit(X, T, Xv, Tv, n_trees=args.trees, depth=d) for d in args.depth]
+        best = max(range(len(models)), key=lambda i: models[i]["validation_score"])
+        models[best]["depth"] = args.depth[best]
+        return models[best]
+
+    m = fit_best(Xall[itr], Tall[itr], Xall[iva], Tall[iva])
     report("pooled 40/10/50 split, test half (Sec. 5.2 protocol)", Tall[ite], predict(m, Xall[ite]), lines)
     # (b) shipped model: trained on the training sets only (10 % of them held out to pick the
     #     number of trees), scored on the never-seen evaluation sweep
     perm = np.random.RandomState(2).permutation(len(Xtr))
     nv = max(1, len(perm) // 10)
-    model = fit(Xtr[perm[nv:]], Ttr[perm[nv:]], Xtr[perm[:nv]], Ttr[perm[:nv]], n_trees=args.trees, depth=args.depth)
+    model = fit_best(Xtr[perm[nv:]], Ttr[perm[nv:]], Xtr[perm[:nv]], Ttr[perm[:nv]])
     report("evaluation sweep (64 matrices x 6 N, disjoint seeds from training)", Tev, predict(model, Xev), lines)
     report("training sets (resubstitution)", Ttr, predict(model, Xtr), lines)
     for p in args.also_score:
@@ -181,10 +190,11 @@ def main():
     for label, Xf in (("paper's 4 features (nnz, mat_size, std_row, N)", paper4),
                       ("without the dispersion features (rows, nnz, mean, N)", Xall[:, [0, 1, 2, 5]]),
                       ("all 7 features", Xall)):
-        mm = fit(Xf[itr], Tall[itr], Xf[iva], Tall[iva], n_trees=args.trees, depth=args.depth)
+        mm = fit_best(Xf[itr], Tall[itr], Xf[iva], Tall[iva])
         lines.append(f"ablation, pooled 40/10/50 test half, {label}: "
                      f"{normalized_performance(Tall[ite], predict(mm, Xf[ite])):.4f}")
-    lines.append(f"model: {len(model['trees'])} trees, depth <= {args.depth}; "
+    lines.append(f"model: {len(model['trees'])} trees, depth <= {model['depth']} (picked among {args.depth} and up to "
+                 f"{args.trees} trees by the held-out tenth of the training sets); "
                  f"trained on {len(Xtr)} inputs from {', '.join(os.path.basename(p) for p in args.train)}")
     text = "\n".join(lines)
     print(text)
