@@ -1,9 +1,12 @@
 """Train the data-aware selector (paper Sec. 5) from sweep timings and compile it into the library.
 
+    D=paper_2202_08556_amd/selector_data
     python -m paper_2202_08556_amd.selector_train \
-        --train paper_2202_08556_amd/selector_data/train.jsonl paper_2202_08556_amd/selector_data/families.jsonl \
-        --eval paper_2202_08556_amd/selector_data/eval.jsonl \
-        --also-score paper_2202_08556_amd/selector_data/odd.jsonl
+        --train $D/train.jsonl $D/families.jsonl $D/train_N2_N4.jsonl --eval $D/eval.jsonl \
+        --also-score $D/odd.jsonl $D/eval_N2_N4.jsonl $D/odd_N2_N4.jsonl
+
+(train_N2_N4.jsonl = the train and families sweeps run again with --ns 2,4; eval_N2_N4 and odd_N2_N4
+likewise for the two never-trained-on sets.)
 
 The paper trains a gradient-boosted tree classifier (LightGBM) on `nnz, mat_size, std_row, N`
 (Table 2).  LightGBM is not available here, so the model is a small gradient-boosted forest built

@@ -15,6 +15,8 @@ Sets
             for training only
   odd       other members of those odd shapes (different sizes and seeds), never trained on
 
+--ns 2,4 runs the same matrices at other dense widths (the paper also reports N = 2).
+
 One JSON line per (matrix, N): features as returned by da_spmm_features, and the time of each id
 in microseconds (HIP events around a batch of back-to-back calls that rotate over 3 copies of B
 and C).  Points already present in the output file are skipped, so a run can be resumed.
@@ -171,7 +173,9 @@ def main():
     ap.add_argument("--members", default=None)
     ap.add_argument("--out", required=True)
     ap.add_argument("--max-seconds", type=float, default=1e9, help="stop starting new matrices after this")
+    ap.add_argument("--ns", default=None, help="comma-separated dense widths instead of 8,16,32,64,128,256")
     args = ap.parse_args()
+    ns = tuple(int(x) for x in args.ns.split(",")) if args.ns else NS
     done = set()
     if os.path.exists(args.out):
         for line in open(args.out):
@@ -185,23 +189,23 @@ def main():
         if args.set in ("families", "odd"):
             members = family_members() if args.set == "families" else odd_members(7800, train=False)
             for idx, (name, make) in enumerate(members):
-                if all((args.set, name, N) in done for N in NS):
+                if all((args.set, name, N) in done for N in ns):
                     continue
                 if time.time() - t0 > args.max_seconds:
                     break
-                run_matrix(make(), name, idx, args.set, out, done)
+                run_matrix(make(), name, idx, args.set, out, done, ns)
         else:
             base, cap = (5000, 2 ** 26) if args.set == "eval" else (100000, 2 ** 24)
             members = parse_members(args.members or ("0-63" if args.set == "eval" else "0-255"))
             for j in members:
                 tag = f"sweep{j}"
-                if all((args.set, tag, N) in done for N in NS):
+                if all((args.set, tag, N) in done for N in ns):
                     continue
                 if time.time() - t0 > args.max_seconds:
                     break
                 m, mean_len, cv, seed = gen.sweep_params(j, base, cap)
                 a = gen.lognormal_csr(m, mean_len, cv, seed, name=tag)
-                run_matrix(a, tag, j, args.set, out, done)
+                run_matrix(a, tag, j, args.set, out, done, ns)
     print("sweep finished", flush=True)
 
 
