@@ -120,8 +120,8 @@ int da_spmm_ex(int64_t m, int64_t k, int64_t N,
 
 /*
  * Data-aware algorithm choice (Sec. 5.1): maps input characteristics to an algorithm id 0..7 by
- * walking a decision tree compiled into the library (trained offline on this GPU on seeded
- * synthetic matrices).  `f` is a HOST pointer.  Pure and deterministic; no device work.
+ * walking a forest of boosted regression trees compiled into the library (trained offline on this
+ * GPU on seeded synthetic matrices; each tree adds to a score per id, the best score wins).  `f` is a HOST pointer.  Pure and deterministic; no device work.
  * Returns the id, or a negative da_status (-DA_ERR_INVALID_ARG) when f is NULL or holds
  * negative / non-finite entries.
  */
@@ -206,8 +206,8 @@ int da_csr_validate(int64_t m, int64_t k, int64_t nnz, const int32_t *rowptr, co
  *            the call; inside every row of A^T the indices ascend (entries of equal (row, column)
  *            keep their stored order), so the result is deterministic bit for bit
  *   workspace  device scratch of at least the size da_csr_transpose_workspace reports for the
- *            same (m, k, nnz) (about 24 bytes per stored entry), 256-byte aligned, owned by the caller, free for reuse once the
- *            stream has passed the call; may be NULL when nnz == 0
+ *            same (m, k, nnz) (about 24 bytes per stored entry), 256-byte aligned, owned by the
+ *            caller, free for reuse once the stream has passed the call; may be NULL when nnz == 0
  * The call allocates nothing, only enqueues kernels on `stream` and does not synchronise.  Inputs
  * and outputs must not overlap.  As for da_spmm, the arrays are trusted to be well formed.
  * Errors: DA_ERR_INVALID_ARG (negative or too large sizes, null arrays with nnz > 0, workspace
