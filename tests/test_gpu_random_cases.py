@@ -17,8 +17,12 @@ def draw_case(seed):
     rng = np.random.default_rng(seed)
     m = int(rng.integers(1, 3000))
     k = int(rng.integers(1, 3000))
-    kind = int(rng.integers(0, 4))
-    if kind == 0:
+    kind = int(rng.integers(0, 5))
+    if kind == 4:                                    # stored rows between long runs of empty rows
+        m = int(rng.integers(1000, 30000))
+        a = gen.hypersparse_csr(m, k, row_frac=float(rng.uniform(0.002, 0.2)), mean_len=float(rng.uniform(1.0, min(k, 40))),
+                                seed=seed)
+    elif kind == 0:
         a = gen.uniform_csr(m=m, k=k, mean_len=float(rng.uniform(0.2, min(k, 40))), seed=seed)
     elif kind == 1:
         a = gen.lognormal_csr(m, float(rng.uniform(1.0, min(k, 60))), float(rng.uniform(0.0, 8.0)), seed=seed, k=k,
