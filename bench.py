@@ -192,6 +192,11 @@ def main():
                      "traffic": measured_traffic(args.workload, N, da.ALGO_NAMES[chosen]),
                      "kernel": f"da_spmm({da.ALGO_NAMES[chosen]}) incl. EB zero pre-pass",
                      "algorithmic_bytes_per_launch": cbytes},
+        # second lower bound: every multiply-add takes a fresh 4-byte B operand out of the cache hierarchy;
+        # 32 TB/s is what a stand-alone gather of 512-byte rows from an L2-resident table reaches here
+        "on_chip_gather_bound": {"bytes": 4 * a.nnz * N, "rate_TBps": 32.0,
+                                 "us": round(4 * a.nnz * N / 32.0e6, 1),
+                                 "frac_of_measured": round(4 * a.nnz * N / 32.0e6 / (ms * 1e3), 3)},
         "features_ms_once_per_matrix": round(feat_ms, 3), "features_ms_first_call": round(feat_first_ms, 3),
         "select_us_per_call": round(select_us, 3),
         "prepare_ms_once_per_matrix": None if prep_ms is None else round(prep_ms, 3),
