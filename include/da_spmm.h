@@ -155,10 +155,17 @@ int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, 
  * like da_spmm_features does.  A kernel that finds another nnz on the device than the plan was
  * built for ignores the plan, so a stale plan costs speed, never correctness; the contents of
  * colind may change freely.  Allocates and frees temporary device memory, synchronises `stream`.
- * Prepare, release and the product calls may be issued from several host threads: a plan is freed
- * only after the kernels already launched with it have finished (the free waits for the device).
- * A HIP graph captured from an EB call on a prepared matrix holds the address of the plan's order:
- * keep the plan (no release, no re-prepare, fewer than 16 later prepares) while the graph is replayed.
+ * Prepare, release and the product calls may be issued from several host threads; product calls do
+ * not serialise each other (the plan table is locked only for the lookup; the plan's memory is
+ * reference-counted and freed only after every call that looked it up has launched, and the free
+ * itself waits for launched kernels).
+ * A HIP graph captured from an EB call on a prepared matrix holds the address of the plan's order.
+ * The library notices the capture and from then on never frees that plan by itself (no eviction by
+ * later prepares; a re-prepare of the same matrix keeps it): only da_spmm_release frees it, which
+ * the caller must not do while the graph is still replayed.  da_spmm_release(NULL) also frees plans
+ * that a re-prepare with another nnz has set aside.
+ * These two host tables (nnz hints, plans) are the library's only mutable global state; both only
+ * steer launch geometry and chunk order, never the result.
  *
  * da_eb_schedule is the building block: order[u], u = 0 .. ceil(nnz/unit)-1, lists the chunk
  * numbers (chunk c = stored entries [c*unit, (c+1)*unit)) sorted by a key in [0, 2k), ties in

@@ -13,7 +13,6 @@ Contents (each cites the passage of the paper it follows):
                           pass of the aggregation step of a graph-convolution layer (Sec. 6, GCN)
   csr_transpose           CSR arrays of A^T with ascending indices inside every row
   gcn_layer / gcn_layer_backward   relu(A.(X.W) + b) and its gradients in fp64 (Sec. 6, GCN)
-  eb_schedule             order in which EB workers take their chunks (column sweep; multi-row chunks apart)
   features                input characteristics of Sec. 5.1, Table 2 (nnz, matrix size, standard
                           deviation of row lengths, N) plus mean / max row length
   conditional_reduction   the conditional prefix-sum network of Sec. 4 (EB+RM+PR, Fig. 6(e)),
@@ -211,32 +210,6 @@ def gcn_layer_backward(rowptr, colind, vals, X, W, Z, d_out, relu: bool = True):
         for p in range(rp[i], rp[i + 1]):
             dH[ci[p]] += va[p] * dZ[i]
     return dH @ W.T, X.T @ dH, dZ.sum(axis=0)
-
-
-def eb_schedule(rowptr, colind, unit: int, k: int):
-    """(order, first_segment): chunk numbers 0 .. ceil(nnz/unit)-1 of the element-balanced partition
-    (Sec. 3.2: a worker owns `unit` consecutive stored entries) in the order in which the workers
-    take them -- ascending key, ties by chunk number -- and the number of chunks of the first
-    segment.  A chunk inside one row has key k + (first + last column index) // 2 (the middle of the
-    column range it covers).  A chunk that touches several rows is keyed by its first column index
-    alone: these chunks come first and form the first segment.  Any permutation gives the same
-    product; this one makes concurrently running workers touch neighbouring rows of the dense
-    operand and keeps the two kinds of chunk apart."""
-    rowptr = np.asarray(rowptr, dtype=np.int64)
-    colind = np.asarray(colind, dtype=np.int64)
-    nnz = colind.size
-    nunits = -(-nnz // unit)
-    keys = np.zeros(nunits, dtype=np.int64)
-    several = np.zeros(nunits, dtype=bool)
-    for c in range(nunits):
-        first, last = c * unit, min((c + 1) * unit, nnz) - 1
-        row_first = int(np.searchsorted(rowptr, first, side="right")) - 1     # last row starting at or before `first`
-        if last < rowptr[row_first + 1]:
-            keys[c] = k + (colind[first] + colind[last]) // 2
-        else:
-            several[c] = True
-            keys[c] = colind[first]
-    return np.argsort(keys, kind="stable").astype(np.int32), int(several.sum())
 
 
 # --------------------------------------------------------------------------------------------

@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <mutex>
 
 namespace {
@@ -107,16 +108,24 @@ int64_t lookup_nnz(const void* rowptr, int64_t m) {
 }
 
 // Chunk schedules of matrices prepared with da_spmm_prepare, keyed like the nnz hints.  The
-// orders live in one library-owned device allocation per matrix.
+// orders live in one library-owned device allocation per matrix, held through a reference count:
+// a product call copies the reference under the mutex, launches outside it and drops the reference
+// after the launch, so that a concurrent release / re-prepare / eviction can free the memory only
+// once no call is between its lookup and its launch (hipFree itself waits for launched kernels).
 constexpr int kPlanUnits[4] = {64, 128, 256, 512};
+struct DeviceBlock {
+    void* p = nullptr;
+    ~DeviceBlock() { if (p) (void)hipFree(p); }
+};
 struct Plan {
-    const void* rowptr;
-    const void* colind;
-    int64_t m, nnz;
-    int* order[4];
-    int units[4];
-    int first_units[4];   // chunks of the first schedule segment (multi-row chunks, when they go first)
-    void* block;
+    const void* rowptr = nullptr;
+    const void* colind = nullptr;
+    int64_t m = 0, nnz = 0;
+    int* order[4] = {nullptr, nullptr, nullptr, nullptr};
+    int units[4] = {0, 0, 0, 0};
+    int first_units[4] = {0, 0, 0, 0};   // chunks of the first schedule segment (multi-row chunks)
+    std::shared_ptr<DeviceBlock> block;
+    bool captured = false;               // a stream capture recorded a kernel that reads the orders
 };
 std::mutex g_plan_mu;
 Plan g_plans[16];
@@ -130,15 +139,21 @@ bool has_plan(const void* rowptr, const void* colind, int64_t m) {
 }
 
 // Schedule of a prepared matrix for this chunk size; split holds the CHUNKS of the first segment
-// here, the launch turns it into blocks.  The caller holds g_plan_mu from this lookup until the
-// kernel that reads the order has been launched: plans are freed only under that mutex, and hipFree
-// waits for work already launched, so the order cannot disappear under a kernel.
-Schedule lookup_schedule_locked(const void* rowptr, const void* colind, int64_t m, int chunk) {
-    for (const auto& pl : g_plans)
+// here, the launch turns it into blocks.  *keep receives a reference to the plan's memory, to be
+// held until the kernel that reads the order has been launched.  capturing: the launch is being
+// recorded into a HIP graph, which will read the order on every replay: such a plan is never
+// evicted or replaced behind the caller's back, only da_spmm_release frees it.
+Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int chunk, bool capturing,
+                         std::shared_ptr<DeviceBlock>* keep) {
+    std::lock_guard<std::mutex> lk(g_plan_mu);
+    for (auto& pl : g_plans)
         if (pl.block && pl.rowptr == rowptr && pl.colind == colind && pl.m == m)
             for (int i = 0; i < 4; ++i)
-                if (kPlanUnits[i] == chunk)
+                if (kPlanUnits[i] == chunk) {
+                    *keep = pl.block;
+                    if (capturing) pl.captured = true;
                     return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0, pl.first_units[i], 0, 0, 0};
+                }
     return Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0};
 }
 
@@ -257,9 +272,12 @@ int launch_w(Family fam, const Problem& p, const Geometry& geo) {
         const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
         hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.C, chunk);
         // chunk order of a prepared matrix (column sweep), if one exists for this chunk size
-        std::lock_guard<std::mutex> plan_lock(g_plan_mu);
-        Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0) ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0}
-                                                         : lookup_schedule_locked(p.rowptr, p.colind, p.m, chunk);
+        std::shared_ptr<DeviceBlock> keep;                 // dropped after the launch
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(p.stream, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
+        Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0)
+                           ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0}
+                           : lookup_schedule(p.rowptr, p.colind, p.m, chunk, cap == hipStreamCaptureStatusActive, &keep);
         const int first_chunks = sch.split;
         sch.split = 0;
         if (sch.order && !pin && geo.stripe > 0) {
@@ -648,15 +666,18 @@ int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, con
 
 int da_spmm_release(const int32_t* rowptr)
 {
-    std::lock_guard<std::mutex> lk(g_plan_mu);
-    hipError_t e = hipSuccess;
-    for (auto& pl : g_plans)
-        if (pl.block && (!rowptr || pl.rowptr == rowptr)) {
-            const hipError_t f = hipFree(pl.block);
-            if (f != hipSuccess) e = f;
-            pl = Plan{};
-        }
-    if (e != hipSuccess) return hip_fail(e, "da_spmm_release");
+    // the references are dropped outside the mutex: the last one frees device memory, which waits
+    // for the device
+    std::shared_ptr<DeviceBlock> dropped[16];
+    {
+        std::lock_guard<std::mutex> lk(g_plan_mu);
+        int n = 0;
+        for (auto& pl : g_plans)
+            if (pl.block && (!rowptr || pl.rowptr == rowptr)) {
+                dropped[n++] = std::move(pl.block);
+                pl = Plan{};
+            }
+    }
     return DA_OK;
 }
 
@@ -672,7 +693,7 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
         if (v != DA_OK) return v;
     }
     if (k > (1LL << 30)) { remember_nnz(rowptr, m, nnz); return DA_OK; }    // no schedule for such widths
-    Plan pl{};
+    Plan pl;
     pl.rowptr = rowptr; pl.colind = colind; pl.m = m; pl.nnz = nnz;
     size_t ints = 64, ws_bytes = 0;                        // the first 4 ints receive the segment sizes
     for (int i = 0; i < 4; ++i) {
@@ -681,34 +702,52 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
         const size_t b = plan_transpose(2 * k, pl.units[i]).bytes;
         ws_bytes = b > ws_bytes ? b : ws_bytes;
     }
-    void* ws = nullptr;
-    hipError_t e = hipMalloc(&pl.block, ints * sizeof(int));
+    pl.block = std::make_shared<DeviceBlock>();
+    DeviceBlock ws;
+    hipError_t e = hipMalloc(&pl.block->p, ints * sizeof(int));
     if (e != hipSuccess) return hip_fail(e, "hipMalloc");
-    e = hipMalloc(&ws, ws_bytes);
-    if (e != hipSuccess) { (void)hipFree(pl.block); return hip_fail(e, "hipMalloc"); }
+    e = hipMalloc(&ws.p, ws_bytes);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc");
     int status = DA_OK;
     size_t off = 64;
-    int* seg = static_cast<int*>(pl.block);
+    int* seg = static_cast<int*>(pl.block->p);
     for (int i = 0; i < 4 && status == DA_OK; ++i) {
-        pl.order[i] = static_cast<int*>(pl.block) + off;
+        pl.order[i] = seg + off;
         off += (size_t)((pl.units[i] + 63) & ~63);
-        status = da_eb_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], seg + i, ws, ws_bytes, stream);
+        status = da_eb_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], seg + i, ws.p, ws_bytes, stream);
     }
     e = hipSuccess;
     if (status == DA_OK)
         e = hipMemcpyAsync(pl.first_units, seg, sizeof pl.first_units, hipMemcpyDeviceToHost, (hipStream_t)stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
-    (void)hipFree(ws);
     if (status == DA_OK && e != hipSuccess) status = hip_fail(e, "da_spmm_prepare");
-    if (status != DA_OK) { (void)hipFree(pl.block); return status; }
+    if (status != DA_OK) return status;
     remember_nnz(rowptr, m, nnz);
-    std::lock_guard<std::mutex> lk(g_plan_mu);
-    Plan* slot = nullptr;
-    for (auto& q : g_plans)
-        if (q.block && q.rowptr == rowptr && q.m == m) { slot = &q; break; }      // replace an older plan of this matrix
-    if (!slot) { slot = &g_plans[g_plan_next]; g_plan_next = (g_plan_next + 1) % 16; }
-    if (slot->block) (void)hipFree(slot->block);
-    *slot = pl;
+    std::shared_ptr<DeviceBlock> old;                      // freed after the mutex is released
+    {
+        std::lock_guard<std::mutex> lk(g_plan_mu);
+        Plan* slot = nullptr;
+        for (auto& q : g_plans)
+            if (q.block && q.rowptr == rowptr && q.m == m) { slot = &q; break; }  // an older plan of this matrix
+        if (slot && slot->captured) {
+            // A recorded graph reads the old orders on every replay: they stay.  When they describe
+            // the same matrix shape the old plan simply remains in use; otherwise the new one takes
+            // another slot and the old one lives on until da_spmm_release.
+            if (slot->colind == colind && slot->nnz == nnz) return DA_OK;
+            slot->rowptr = nullptr;                        // no longer found by lookups; memory kept
+            slot = nullptr;
+        }
+        if (!slot) {
+            for (int tries = 0; tries < 16 && !slot; ++tries) {
+                Plan* cand = &g_plans[g_plan_next];
+                g_plan_next = (g_plan_next + 1) % 16;
+                if (!(cand->block && cand->captured)) slot = cand;
+            }
+            if (!slot) return DA_OK;                       // every slot is pinned by a graph: no plan for this matrix
+        }
+        old = std::move(slot->block);
+        *slot = pl;
+    }
     return DA_OK;
 }
 

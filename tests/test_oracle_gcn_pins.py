@@ -157,31 +157,3 @@ def test_gcn_layer_forward_and_gradients():
             args_m[which][idx] -= h
             fd = (loss(*args_p) - loss(*args_m)) / (2 * h)
             assert abs(fd - grad[idx]) < 1e-6 * max(1.0, abs(grad[idx]))
-
-
-# T7 -- the chunk order: a permutation sorted by key with ties by chunk number, against Python's
-#       tuple sort over keys derived from per-entry row numbers; the multi-row chunks form the
-#       first segment (matrices with many and with few of them) --------------------------------------
-@pytest.mark.parametrize("unit,light_mean", [(1, 3.0), (4, 3.0), (7, 0.05), (64, 3.0), (16, 0.05)])
-def test_eb_schedule_is_sorted_permutation(unit, light_mean):
-    a = gen.skewed_csr(m=400, k=300, heavy_frac=0.05, heavy_lo=150, heavy_hi=290, light_mean=light_mean, seed=45)
-    order, first_segment = orc.eb_schedule(a.rowptr, a.colind, unit, a.k)
-    nnz = a.colind.size
-    nunits = -(-nnz // unit)
-    assert sorted(order.tolist()) == list(range(nunits))
-    row_of = np.repeat(np.arange(a.m), np.diff(a.rowptr))
-    several = [len(set(row_of[c * unit:min((c + 1) * unit, nnz)].tolist())) > 1 for c in range(nunits)]
-    keyed = []
-    for c in range(nunits):
-        first, last = c * unit, min((c + 1) * unit, nnz) - 1
-        if several[c]:
-            keyed.append((int(a.colind[first]), c))
-        else:
-            keyed.append((a.k + (int(a.colind[first]) + int(a.colind[last])) // 2, c))
-    assert order.tolist() == [c for _, c in sorted(keyed)]
-    assert first_segment == sum(several)
-    # the first segment is exactly the multi-row chunks
-    assert sorted(order[:first_segment].tolist()) == [c for c in range(nunits) if several[c]]
-    if unit >= 16:
-        assert any(several) and not all(several)
-        assert (4 * sum(several) >= nunits) == (light_mean > 1.0)    # many in one case, few in the other
