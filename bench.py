@@ -1,11 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the DA-SpMM hot path on one MI355X.
 
-One "step" = one pass of the hot path over the workload: data-aware algorithm selection
-(da_spmm_select on the features of A, extracted once per matrix as in the paper's use where A is
-static across calls) followed by da_spmm with the chosen algorithm (for EB ids: zero pre-pass +
-product kernel).  Inputs are resident in HBM before the timed region; between steps the call
-rotates over several copies of (A, B, C) so that no step replays the previous one from cache.
+One "step" = one pass of the hot path over the workload: da_spmm with the algorithm the data-aware
+selector picked for this matrix and N (for EB ids: zero pre-pass + product kernel).  Feature
+extraction, selection and the chunk-order preparation happen once per matrix, as in the paper's use
+where A is static across calls (Sec. 5.1); they are timed separately and reported beside the step
+time.  Inputs are resident in HBM before the timed region; between steps the call rotates over
+several copies of (A, B, C) so that no step replays the previous one from cache.
 
 Prints ONE JSON line: SpMM GFLOP/s (2*nnz*N/t) as `value`, plus `roofline` (compulsory bytes
 4(m+1) + 8 nnz + 4kN + 4mN over the measured time per call against 8 TB/s of HBM) and
@@ -54,22 +55,46 @@ def make_workload(name: str, N: int):
 
 
 def measured_traffic(workload: str, N: int, algo_name: str):
-    """HBM bytes per da_spmm call from the committed rocprofv3 counter summary of this workload
-    (FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy kernel's reading), or None when no
-    summary exists for this workload / algorithm."""
+    """(HBM-side bytes per da_spmm call, L2 hit rate, note) from the committed rocprofv3 counter
+    summary of this workload (FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy kernel's
+    reading; written by paper_2202_08556_amd.profile_summary).  The summary is only used when it
+    was measured on the kernel sources this run uses (same source hash) and for the same
+    algorithm; otherwise the traffic is reported as null."""
+    from paper_2202_08556_amd import profile_summary as ps
     path = os.path.join(ROOT, "profiles", f"da_spmm_{workload}_N{N}_hbm_traffic.txt")
+    vals = ps.read_summary(path)
+    if not vals:
+        return None, None, "no counter summary for this workload under profiles/"
+    if vals.get("SOURCE_SHA256") != ps.source_hash():
+        return None, None, "counter summary under profiles/ was measured on other kernel sources"
+    if vals.get("ALGO") != algo_name:
+        return None, None, f"counter summary under profiles/ is for {vals.get('ALGO')}"
     try:
-        vals = {}
-        for line in open(path):
-            if "=" in line and line.split("=")[0].strip() in ("ALGO", "FETCH_KIB_PER_CALL_SCALED",
-                                                              "WRITE_KIB_PER_CALL_SCALED"):
-                k, v = line.split("=", 1)
-                vals[k.strip()] = v.strip()
-        if vals.get("ALGO") != algo_name:
-            return None
-        return int((float(vals["FETCH_KIB_PER_CALL_SCALED"]) + float(vals["WRITE_KIB_PER_CALL_SCALED"])) * 1024)
-    except (OSError, KeyError, ValueError):
+        total = int((float(vals["FETCH_KIB_PER_CALL_SCALED"]) + float(vals["WRITE_KIB_PER_CALL_SCALED"])) * 1024)
+        hit = float(vals["TCC_HIT_RATE"]) if vals.get("TCC_HIT_RATE", "n/a") != "n/a" else None
+    except (KeyError, ValueError):
+        return None, None, "counter summary under profiles/ is incomplete"
+    return total, hit, os.path.relpath(path, ROOT)
+
+
+def stream_ceiling():
+    """Copy and read bandwidth of this machine in TB/s, from the stand-alone `ceilings stream` tool (a
+    child process; 1 GiB buffers), or None when the tool has not been built."""
+    import re
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2202_08556_amd", "ceilings")
+    if not os.path.exists(exe):
         return None
+    try:
+        out = subprocess.run([exe, "stream"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True,
+                             timeout=120).stdout
+    except Exception:
+        return None
+    copy = [float(x) for x in re.findall(r"copy .*? ([0-9.]+) TB/s", out)]
+    read = [float(x) for x in re.findall(r"read .*? ([0-9.]+) TB/s", out)]
+    if not copy or not read:
+        return None
+    return {"copy_TBps": max(copy), "read_TBps": max(read)}
 
 
 def compulsory_bytes(m, k, nnz, N):
@@ -134,19 +159,19 @@ def main():
         prep_ms = (time.perf_counter() - t1) * 1e3
         for c in copies[1:]:
             da.da_spmm_prepare(a.m, a.k, a.nnz, c["rp"], c["ci"])
+    # a1: selection, once per matrix (Sec. 5.1: the choice depends on the matrix and N only)
+    fstruct = da._to_struct(feats)
     t1 = time.perf_counter()
     for _ in range(1000):
-        sel = da.da_spmm_select(feats)
+        sel = da.da_spmm_select(fstruct)
     select_us = (time.perf_counter() - t1) * 1e3
     fixed = None if args.algo == "auto" else int(args.algo)
+    chosen = sel if fixed is None else fixed
 
-    fstruct = da._to_struct(feats)
     runs = [da.PreparedSpmm(a.m, a.k, N, c["rp"], c["ci"], c["va"], c["B"], c["C"]) for c in copies]
 
     def step(i, algo=None):
-        al = algo if algo is not None else (fixed if fixed is not None else da.da_spmm_select(fstruct))
-        runs[i % len(runs)](al)
-        return al
+        runs[i % len(runs)](chosen if algo is None else algo)
 
     def timed(nsteps, warm, algo=None):
         for i in range(warm):
@@ -160,6 +185,18 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / nsteps          # ms per step
 
+    def per_step(nsteps, algo=None):
+        """(median, min) ms over steps timed one by one with an event pair each."""
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(nsteps + 1)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for i in range(nsteps):
+            step(i, algo)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(nsteps))
+        return ts[len(ts) // 2], ts[0]
+
     flops = 2.0 * a.nnz * N
     cbytes = compulsory_bytes(a.m, a.k, a.nnz, N)
 
@@ -172,13 +209,14 @@ def main():
                 f"{cbytes / ms / 1e6 / HBM_PEAK_GBS * 100:5.1f}% of HBM peak")
 
     ms = timed(args.steps, args.warmup)
-    chosen = step(0)
-    torch.cuda.synchronize()
+    median_ms, min_ms = per_step(min(args.steps, 100))
     gflops = flops / ms / 1e6
     achieved = cbytes / ms / 1e6                      # GB/s
     log(f"selected {da.ALGO_NAMES[chosen]}: {ms * 1e3:.1f} us/step, {gflops:.1f} GFLOP/s, "
         f"{achieved:.1f} GB/s compulsory = {achieved / HBM_PEAK_GBS * 100:.1f}% of HBM peak")
 
+    traffic, l2_hit, traffic_note = (measured_traffic(args.workload, N, da.ALGO_NAMES[chosen])
+                                      if not args.no_prepare else (None, None, "summaries are of prepared matrices"))
     out = {
         "metric": "SpMM GFLOP/s (2*nnz*N/t)", "value": round(gflops, 2), "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 6),
@@ -187,9 +225,10 @@ def main():
         "config": {"workload": f"{args.workload} N={N}: {desc}", "m": a.m, "k": a.k, "nnz": a.nnz,
                    "N": N, "algo": da.ALGO_NAMES[chosen], "selected_by": "da_spmm_select" if fixed is None else "fixed",
                    "copies_rotated": len(copies)},
+        "median_ms": round(median_ms, 6), "min_ms": round(min_ms, 6),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(args.workload, N, da.ALGO_NAMES[chosen]),
+                     "traffic": traffic, "traffic_source": traffic_note, "l2_hit_rate": l2_hit,
                      "kernel": f"da_spmm({da.ALGO_NAMES[chosen]}) incl. EB zero pre-pass",
                      "algorithmic_bytes_per_launch": cbytes},
         # second lower bound: every multiply-add takes a fresh 4-byte B operand out of the cache hierarchy;
@@ -227,6 +266,12 @@ def main():
     except Exception as exc:                               # graph capture is optional information
         out["graph_replay_us_per_call"] = None
         log(f"graph capture skipped: {exc}")
+    # the same call on matrices that were never prepared (no chunk order): what a caller gets who
+    # skips the once-per-matrix da_spmm_prepare
+    if not args.no_prepare:
+        da.da_spmm_release()
+        out["unprepared_ms"] = round(timed(max(5, args.steps // 4), 3), 6)
+    out["stream_ceiling"] = stream_ceiling()
     if variants:
         best = min(variants.values())
         out["variants_ms"] = variants
