@@ -226,6 +226,28 @@ int da_csr_transpose(int64_t m, int64_t k, int64_t nnz,
                      int32_t *t_rowptr, int32_t *t_colind, float *t_vals,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * da_csr_transpose for callers that cannot allocate device memory and have no workspace to hand
+ * over: code that runs under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (without the workspace), same kernels and bit-for-bit the same result
+ * as da_csr_transpose; the radix passes run in a static device array of DA_NOALLOC_SCRATCH_BYTES
+ * (32 MiB) that every GPU the library is loaded on holds until the process ends.  The call
+ * allocates and frees nothing and does not synchronise; it skips the DA_SPMM_DEBUG_VALIDATE check
+ * (which allocates).
+ * Limit: da_csr_transpose_workspace(m, k, nnz) must not exceed DA_NOALLOC_SCRATCH_BYTES (about
+ * 1.39 million stored entries); beyond it the call returns DA_ERR_UNSUPPORTED, enqueues nothing
+ * and the last-error text says so.
+ * All calls on one GPU share that GPU's array: calls whose execution can overlap on one GPU
+ * (different streams, different host threads) race on it -- order them on one stream or with
+ * events.  Nothing in the array needs clearing between calls (every part is written before it is
+ * read within a call).  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress); make that first call outside a stream capture.
+ */
+#define DA_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+int da_csr_transpose_noalloc(int64_t m, int64_t k, int64_t nnz,
+                             const int32_t *rowptr, const int32_t *colind, const float *vals,
+                             int32_t *t_rowptr, int32_t *t_colind, float *t_vals, void *stream);
+
 /* "RB+RM+SR" ... "EB+CM+PR" (Table 1 naming); NULL for an id outside 0..7.  Host string, static. */
 const char *da_spmm_algo_name(int algo);
 

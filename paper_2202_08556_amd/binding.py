@@ -23,7 +23,7 @@ DA_OK, DA_ERR_INVALID_ARG, DA_ERR_BAD_ALGO, DA_ERR_UNSUPPORTED, DA_ERR_HIP = ran
 DA_NUM_ALGOS = 8
 DA_ROW_MAJOR, DA_COL_MAJOR = 0, 1
 EXPORTS = ("da_spmm", "da_spmm_ex", "da_spmm_select", "da_spmm_features", "da_csr_transpose_workspace",
-           "da_csr_transpose", "da_csr_validate", "da_spmm_prepare", "da_spmm_release",
+           "da_csr_transpose", "da_csr_transpose_noalloc", "da_csr_validate", "da_spmm_prepare", "da_spmm_release",
            "da_eb_schedule_workspace", "da_eb_schedule", "da_spmm_algo_name", "da_spmm_last_error")
 
 
@@ -47,6 +47,8 @@ _lib.da_csr_transpose_workspace.argtypes = [_i64, _i64, _i64, ctypes.POINTER(cty
 _lib.da_csr_transpose_workspace.restype = ctypes.c_int
 _lib.da_csr_transpose.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.da_csr_transpose.restype = ctypes.c_int
+_lib.da_csr_transpose_noalloc.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.da_csr_transpose_noalloc.restype = ctypes.c_int
 _lib.da_csr_validate.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp]
 _lib.da_csr_validate.restype = ctypes.c_int
 _lib.da_spmm_prepare.argtypes = [_i64, _i64, _i64, _vp, _vp, _vp]
@@ -188,6 +190,19 @@ def da_csr_transpose(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals
                                  workspace_bytes, stream)
     if st != DA_OK:
         raise DaSpmmError(st, da_spmm_last_error())
+
+
+DA_NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def da_csr_transpose_noalloc_status(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, stream=None) -> int:
+    return int(_lib.da_csr_transpose_noalloc(int(m), int(k), int(nnz), _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                             _ptr(t_rowptr), _ptr(t_colind), _ptr(t_vals), _stream(stream)))
+
+
+def da_csr_transpose_noalloc(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, stream=None) -> None:
+    """da_csr_transpose on the library's static scratch: no workspace, no allocation (see include/da_spmm.h)."""
+    _check(da_csr_transpose_noalloc_status(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, stream))
 
 
 def da_csr_validate_status(m, k, nnz, rowptr, colind, stream=None) -> int:

@@ -395,6 +395,40 @@ TransposePlan plan_transpose(int64_t k, int64_t nnz) {
     return t;
 }
 
+int check_transpose_args(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                         const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals);
+int enqueue_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                      const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+// Scratch memory of the entry point that allocates nothing (da_csr_transpose_noalloc): a static
+// device array, one copy per GPU, held from the moment the library is loaded on that GPU until the
+// process ends.  In host code the array's name is only a handle for the runtime, not a device
+// address: the address on the current device is asked for once per device and kept.
+constexpr size_t kScratchBytes = size_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];
+
+int scratch_address(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(DA_ERR_UNSUPPORTED, "device ordinal beyond 63%s");
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p || reinterpret_cast<uintptr_t>(p) % 256 != 0) return fail(DA_ERR_HIP, "static scratch has no usable device address%s");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DA_OK;
+}
+
 // DA_SPMM_DEBUG_VALIDATE=1 makes da_spmm / da_spmm_ex / da_csr_transpose check the CSR arrays on
 // the device before they launch anything (this synchronises the stream)
 bool debug_validate() {
@@ -548,6 +582,37 @@ int da_csr_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, c
                      const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals,
                      void* workspace, size_t workspace_bytes, void* stream)
 {
+    const int st = check_transpose_args(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals);
+    if (st != DA_OK) return st;
+    if (debug_validate() && m > 0) {
+        const int v = da_csr_validate(m, k, nnz, rowptr, colind, stream);
+        if (v != DA_OK) return v;
+    }
+    return enqueue_transpose(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, workspace, workspace_bytes, stream);
+}
+
+int da_csr_transpose_noalloc(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                             const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals, void* stream)
+{
+    const int st = check_transpose_args(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals);
+    if (st != DA_OK) return st;
+    if (plan_transpose(k, nnz).bytes > kScratchBytes)
+        return fail(DA_ERR_UNSUPPORTED,
+                    "da_csr_transpose_noalloc: the sort needs more than the library's 32 MiB static scratch "
+                    "(about 24 bytes per stored entry); use da_csr_transpose with a workspace%s");
+    void* ptr = nullptr;
+    const int sp = scratch_address(&ptr);
+    if (sp != DA_OK) return sp;
+    return enqueue_transpose(m, k, nnz, rowptr, colind, vals, t_rowptr, t_colind, t_vals, ptr, kScratchBytes, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int check_transpose_args(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                         const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals)
+{
     if (m < 0 || k < 0 || nnz < 0) return fail(DA_ERR_INVALID_ARG, "negative size%s");
     if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
         return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
@@ -555,10 +620,16 @@ int da_csr_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, c
     if (nnz > 0 && (m == 0 || k == 0)) return fail(DA_ERR_INVALID_ARG, "stored entries in a matrix without rows or columns%s");
     if (nnz > 0 && (!rowptr || !colind || !vals || !t_colind || !t_vals))
         return fail(DA_ERR_INVALID_ARG, "null array with nnz > 0%s");
-    if (debug_validate() && m > 0) {
-        const int v = da_csr_validate(m, k, nnz, rowptr, colind, stream);
-        if (v != DA_OK) return v;
-    }
+    return DA_OK;
+}
+
+// The radix passes of the transpose on the given scratch memory.  Every part of the scratch that
+// a kernel reads was written earlier in the same call (keys / rows / values of the ping-pong, the
+// whole histogram, every chunk sum), so stale contents of a reused buffer are never seen.
+int enqueue_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                      const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals,
+                      void* workspace, size_t workspace_bytes, void* stream)
+{
     const TransposePlan t = plan_transpose(k, nnz);
     if (nnz > 0 && (!workspace || workspace_bytes < t.bytes))
         return fail(DA_ERR_INVALID_ARG, "workspace missing or smaller than da_csr_transpose_workspace reports%s");
@@ -607,6 +678,10 @@ int da_csr_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, c
     if (e != hipSuccess) return hip_fail(e, "da_csr_transpose launch");
     return DA_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t* bytes)
 {
