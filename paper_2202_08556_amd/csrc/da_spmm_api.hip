@@ -74,7 +74,8 @@ struct Geometry {
 constexpr int kSweepStripe = 256;
 
 constexpr int kMaxGridY = 65535;
-constexpr int kMaxGroupPR = 8;         // RM mapping under PR keeps at least 8 slots along the entries
+constexpr int kMaxGroupPR = 32;        // PR needs at least two slots along the entries
+constexpr int kDefaultGroupPR = 8;     // 4-byte accesses: at least 8 slots along the entries
 constexpr int kEntriesPerWavePR = 512; // EB+PR: stored entries per wave and pass
 
 int env_int(const char* name, int fallback) {
@@ -152,9 +153,9 @@ Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int 
                 if (kPlanUnits[i] == chunk) {
                     *keep = pl.block;
                     if (capturing) pl.captured = true;
-                    return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0, pl.first_units[i], 0, 0, 0};
+                    return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0, pl.first_units[i], 0, 0, 0, 3};
                 }
-    return Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0};
+    return Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3};
 }
 
 // Default geometry per algorithm family and N.  Measured on MI355X: 16-byte and 4-byte gathers
@@ -178,7 +179,10 @@ int pick_geometry(bool cm, bool pr, bool eb, int64_t N, const void* B, const voi
         g.G = pow2_ceil((N + g.V - 1) / g.V);
         // SR: at most 128 columns per tile (32 lanes of 4): at N = 256 two passes over 512-byte row
         // segments keep more rows of B in L2 than one pass over 1 KB rows and were never slower
-        const int cap = pr ? kMaxGroupPR : (g.V == 4 ? 32 : kWave);
+        // PR keeps slots along the entries: with 16-byte accesses 2 under EB (wave per chunk; the
+        // conditional reduction gets shallower as the group widens: power-law N = 128 823 / 645 /
+        // 574 us for groups of 8 / 16 / 32) and 4 under RB (wave per row: 629 / 559 / 636 us)
+        const int cap = g.V == 4 ? ((pr && !eb) ? 16 : 32) : (pr ? kDefaultGroupPR : kWave);
         if (g.G > cap) g.G = cap;
         g.NV = 1;
     }
@@ -276,20 +280,23 @@ int launch_w(Family fam, const Problem& p, const Geometry& geo) {
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(p.stream, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
         Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0)
-                           ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0}
+                           ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3}
                            : lookup_schedule(p.rowptr, p.colind, p.m, chunk, cap == hipStreamCaptureStatusActive, &keep);
         const int first_chunks = sch.split;
         sch.split = 0;
-        if (sch.order && !pin && geo.stripe > 0) {
-            // Deal the schedule to the XCDs in stripes (sweep_block).  Stripe length near geo.stripe
-            // such that whole rounds of 8 stripes cover a segment with next to no surplus (all XCDs
-            // then get the same number of stripes).  When the schedule starts with a segment of
-            // multi-row chunks, that segment and the rest are dealt separately: the two kinds of
-            // chunk cost differently, and every XCD should get the same share of both.
+        if (sch.order && geo.stripe > 0) {
+            // Deal the schedule in stripes (sweep_block) to the XCDs that work on it: all 8, or the
+            // 8 / pin that share a pinned column tile.  Stripe length near geo.stripe such that whole
+            // rounds of stripes cover a segment with next to no surplus (all XCDs then get the same
+            // number of stripes).  When the schedule starts with a segment of multi-row chunks, that
+            // segment and the rest are dealt separately: the two kinds of chunk cost differently,
+            // and every XCD should get the same share of both.
+            const long nx = pin ? 8 / pin : 8;
+            sch.nx_log2 = nx == 8 ? 3 : (nx == 4 ? 2 : (nx == 2 ? 1 : 0));
             const long wpb = fam == EB_SR ? (long)kWavesPerBlock * (kWave / G) : (long)kWavesPerBlock;
             const long nvb = (sch.units + wpb - 1) / wpb;
             auto deal = [&](long nb, int* stripe_out) {        // blocks per XCD, rounded up to whole stripes
-                const long per_xcd = (nb + 7) / 8;
+                const long per_xcd = (nb + nx - 1) / nx;
                 long rounds = (per_xcd + geo.stripe / 2) / geo.stripe;
                 if (rounds < 1) rounds = 1;
                 *stripe_out = (int)((per_xcd + rounds - 1) / rounds);
@@ -302,10 +309,10 @@ int launch_w(Family fam, const Problem& p, const Geometry& geo) {
                 sch.split = (int)split;
                 sch.per_a = (int)deal(split > 0 ? split : nvb, &sch.stripe);
                 if (split > 0) per_b = deal(nvb - split, &sch.stripe_b); else sch.stripe_b = 1;
-                sch.vblocks = (int)(8 * (sch.per_a + per_b));
+                sch.vblocks = (int)(nx * (sch.per_a + per_b));
                 if (blocks >= nvb) blocks = sch.vblocks;      // one chunk per worker
             }
-            blocks = (blocks + 7) / 8 * 8;                 // block b stays on XCD b % 8 on every pass
+            if (!pin) blocks = (blocks + 7) / 8 * 8;       // block b stays on XCD b % 8 on every pass
         }
         if (fam == EB_SR) {
             hipLaunchKernelGGL((eb_sr_kernel<V, G, NV, WIDE>), grid_for(blocks), block, 0, p.stream,

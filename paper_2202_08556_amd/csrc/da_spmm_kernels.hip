@@ -44,18 +44,19 @@ struct Strides {
 // instead of chunk u.  The order is a permutation of 0..units-1 built for a matrix with `nnz`
 // stored entries and the chunk size of the launch; a kernel that finds another nnz on the device
 // ignores it (order == nullptr: no schedule).
-// stripe > 0: the schedule is dealt to the 8 XCDs in stripes (see sweep_block).  The schedule may
-// consist of two segments that are dealt separately, blocks [0, split) in stripes of `stripe`
-// blocks and the rest in stripes of `stripe_b`, so that every XCD gets the same share of both
-// (split == 0: one segment).  per_a = blocks of the first segment per XCD, rounded up to whole
-// stripes; vblocks = number of block positions to walk (8 * blocks per XCD over both segments;
-// positions that fall outside a segment find no chunk).  The grid's x extent must be a multiple of
-// 8 so that a block stays on its XCD when it makes more than one pass.
+// stripe > 0: the schedule is dealt in stripes to the XCDs that work on it (see sweep_block): all 8,
+// or the 8 / pin_tiles XCDs that share a column tile when tiles are pinned to XCDs (nx_log2 = log2
+// of that number).  The schedule may consist of two segments that are dealt separately, blocks
+// [0, split) in stripes of `stripe` blocks and the rest in stripes of `stripe_b`, so that every XCD
+// gets the same share of both (split == 0: one segment).  per_a = blocks of the first segment per
+// XCD, rounded up to whole stripes; vblocks = number of block positions to walk (XCDs * blocks per
+// XCD over both segments; positions that fall outside a segment find no chunk).  The grid's x
+// extent must be a multiple of 8 so that a block stays on its XCD when it makes more than one pass.
 struct Schedule {
     const int* order;
     int units;
     int nnz;
-    int stripe, split, per_a, stripe_b, vblocks;
+    int stripe, split, per_a, stripe_b, vblocks, nx_log2;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -209,6 +210,49 @@ __device__ __forceinline__ float slot_allreduce(float x) {
     return x;
 }
 
+// y[l] = x[l + D] for the lanes l < 64 - D of a wave (the other lanes receive unspecified values):
+// the data movement of one step of the conditional reduction (Sec. 4, Fig. 6(e)), where a slot
+// takes in the partial result of the slot D lanes to its right.  Distance 32 is one lane swap,
+// distance 16 two swaps and a select, distance 1 a single DPP wave shift: no LDS round trip.
+__device__ __forceinline__ unsigned lane_shift_down_32(unsigned x) {
+    return __builtin_amdgcn_permlane32_swap(x, x, false, false)[1];      // lanes 0..31 <- lanes 32..63
+}
+__device__ __forceinline__ unsigned lane_shift_down_16(unsigned x) {
+    // rows of 16 lanes [x0 x1 x2 x3] -> [x1 x2 x3 .]
+    const unsigned z = lane_shift_down_32(x);                             // [x2 x3 x2 x3]
+    const auto r = __builtin_amdgcn_permlane16_swap(x, z, false, false);  // [x0 x2 x2 x2], [x1 x3 x3 x3]
+    return (threadIdx.x & 16) ? r[0] : r[1];
+}
+template <int D>
+__device__ __forceinline__ float lane_shift_down(float xf) {
+    static_assert(D == 1 || D == 2 || D == 4 || D == 8 || D == 16 || D == 32, "power of two below 64");
+    const unsigned x = __float_as_uint(xf);
+    if constexpr (D == 32) {
+        return __uint_as_float(lane_shift_down_32(x));
+    } else if constexpr (D == 16) {
+        return __uint_as_float(lane_shift_down_16(x));
+    } else if constexpr (D == 1) {
+        return __uint_as_float(__builtin_amdgcn_update_dpp(0u, x, 0x130, 0xf, 0xf, false));   // wave_shl:1
+    } else {
+        // Distances 2, 4, 8 would take a DPP row rotation plus the rotation of the next row for the
+        // lanes that wrap around (five operations); the LDS crossbar moves them in one and measured
+        // faster (EB+RM+PR on the power-law matrix at N = 32: 249 against 261 us).
+        return __shfl_down(xf, D, kWave);
+    }
+}
+
+// The log-step network of the conditional reduction over the S = 64/G slots of a wave: in step DS
+// (1, 2, 4, ...) slot s adds the value of slot s + DS when that slot belongs to the same run of
+// equal row indices, i.e. when DS <= dist, the number of slots from s to the end of its run.
+template <int G, int DS>
+__device__ __forceinline__ void conditional_steps(float& x, int dist) {
+    if constexpr (DS * G < kWave) {
+        const float o = lane_shift_down<DS * G>(x);
+        if (DS <= dist) x += o;
+        conditional_steps<G, DS * 2>(x, dist);
+    }
+}
+
 // Smallest r in [lo, hi] with rowptr[r+1] > q: the row that owns stored entry q (rows without
 // entries are skipped).  Requires rowptr[lo] <= q < rowptr[hi+1].
 __device__ __forceinline__ int row_of_entry(const int* __restrict__ rowptr, int lo, int hi, int q) {
@@ -290,22 +334,25 @@ __device__ __forceinline__ BlockMap block_map(int pin_tiles) {
     return b;
 }
 
-// Position in the schedule of (virtual) block vb when the schedule is swept by all XCDs together:
-// workgroups go round-robin to the 8 XCDs, so block vb runs on XCD vb % 8 and is that XCD's
-// (vb / 8)-th block.  Stripe t of XCD x is stripe 8 t + x of the segment: at any time the XCDs work
-// on 8 neighbouring stripes, each on its own, and the rows of B that one L2 has to hold are an
-// eighth of the band all running workers cover.  Returns -1 for a position outside its segment.
+// Position in the schedule of (virtual) block vb when the schedule is swept by nx XCDs together
+// (nx = 8, or 8 / pin_tiles for the XCDs that share a pinned column tile).  Workgroups go
+// round-robin to the 8 XCDs and block_map numbers the blocks of one tile so that block vb runs on
+// the (vb % nx)-th of these XCDs and is that XCD's (vb / nx)-th block.  Stripe t of XCD x is stripe
+// nx t + x of the segment: at any time the XCDs work on nx neighbouring stripes, each on its own,
+// and the rows of B that one L2 has to hold are an nx-th of the band all running workers cover.
+// Returns -1 for a position outside its segment.
 __device__ __forceinline__ long sweep_block(long vb, const Schedule& sch) {
-    const unsigned x = (unsigned)vb & 7u;                 // block counts fit 32 bits
-    unsigned l = (unsigned)(vb >> 3);
+    const unsigned nx = 1u << sch.nx_log2;
+    const unsigned x = (unsigned)vb & (nx - 1u);          // block counts fit 32 bits
+    unsigned l = (unsigned)(vb >> sch.nx_log2);
     if (l < (unsigned)sch.per_a) {
         const unsigned st = (unsigned)sch.stripe, t = l / st;
-        const long sb = (long)(t * 8u + x) * st + (l - t * st);
+        const long sb = (long)(t * nx + x) * st + (l - t * st);
         return (sch.split > 0 && sb >= sch.split) ? -1 : sb;
     }
     l -= (unsigned)sch.per_a;
     const unsigned st = (unsigned)sch.stripe_b, t = l / st;
-    return sch.split + (long)(t * 8u + x) * st + (l - t * st);
+    return sch.split + (long)(t * nx + x) * st + (l - t * st);
 }
 
 // Calls f(Count<UU>, t) for t covering [0, cnt) in blocks of UMAX, then 4, 2, 1 entries, so that
@@ -564,7 +611,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
 
     const long nunits = ((unsigned)nnz + (unsigned)chunk - 1u) / (unsigned)chunk;   // nnz < 2^31
     const bool scheduled = sch.order != nullptr && sch.nnz == nnz && sch.units == nunits;
-    const bool striped = scheduled && pin_tiles <= 0 && sch.stripe > 0;
+    const bool striped = scheduled && sch.stripe > 0;
     constexpr long WPB = kWavesPerBlock * GPW;            // workers per block
     const long nvb = striped ? sch.vblocks : (nunits + WPB - 1) / WPB;   // block positions to walk
     for (long vb = bm.bx; vb < nvb; vb += bm.nbx) {
@@ -674,6 +721,21 @@ __device__ __forceinline__ Acc<V, NV> slots_allreduce(Acc<V, NV> x) {
     return x;
 }
 
+// Inclusive prefix sum of v over the 64 lanes of a wave: log-step scan inside the rows of 16 lanes
+// with DPP row shifts (zeros shifted in), then the totals of the rows below are added.
+__device__ __forceinline__ int wave_inclusive_scan_dpp(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);    // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);    // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);    // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);    // row_shr:8
+    const int t0 = __builtin_amdgcn_readlane(v, 15), t1 = __builtin_amdgcn_readlane(v, 31),
+              t2 = __builtin_amdgcn_readlane(v, 47);
+    const int row = (threadIdx.x >> 4) & 3;
+    return v + (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
+}
+
+constexpr int kStagedChunk = 512;   // EB+PR: largest chunk whose row starts are staged in LDS
+
 template <int V, int G, int NV, bool WIDE>
 __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
@@ -681,8 +743,9 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     int pin_tiles, Schedule sch)
 {
     constexpr int S = kWave / G;
-    constexpr int UU = G < 4 ? G : 4;                     // steps whose gathers are issued together
+    constexpr int UU = G < 4 ? G : 4;                     // steps whose gathers are issued together (8 measured slower)
     __shared__ int4 stage[G > 1 ? kBlock : 1];
+    __shared__ int starts[kWavesPerBlock][kStagedChunk + 2];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int s = lane / G, j = lane % G;
     const BlockMap bm = block_map(pin_tiles);
@@ -692,10 +755,11 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
     float* __restrict__ Cn = C + (long)n0 * sd.cc;
     const int nnz = rowptr[m];
     int4* st = stage + (G > 1 ? wave * kWave : 0);
+    int* cnt = starts[wave];
 
     const long nunits = ((unsigned)nnz + (unsigned)chunk - 1u) / (unsigned)chunk;   // nnz < 2^31
     const bool scheduled = sch.order != nullptr && sch.nnz == nnz && sch.units == nunits;
-    const bool striped = scheduled && pin_tiles <= 0 && sch.stripe > 0;
+    const bool striped = scheduled && sch.stripe > 0;
     const long nvb = striped ? sch.vblocks : (nunits + kWavesPerBlock - 1) / kWavesPerBlock;   // block positions to walk
     for (long vb = bm.bx; vb < nvb; vb += bm.nbx) {
         const long sb = striped ? sweep_block(vb, sch) : vb;
@@ -711,11 +775,40 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
         int cur = -1;                                      // row being accumulated (wave-uniform)
         bool cur_started = false;                          // its first entry lies in this chunk
 
-        // every lane fetches one entry of a batch and finds its row (binary search restricted to
-        // the rows of this chunk) and whether it is the first / last entry of that row
+        // The row of every entry ("row index calculation" of Sec. 3.2).  The rows after the first
+        // that begin inside the chunk are counted per chunk position in LDS, one coalesced pass
+        // over their row pointers; the row of the entry at position p is then the first row plus
+        // the number of row starts at positions 1..p, a prefix sum over the wave, and an entry is
+        // the first / last of its row when a row starts at its own / the next position.  cnt[0]
+        // holds whether the first row starts with the chunk, cnt[c1 - c0] whether the last one ends
+        // with it.  A row range too long to stage (runs of rows without entries) falls back to a
+        // binary search per entry.
+        const int len = c1 - c0;
+        const bool staged = chunk <= kStagedChunk && row_hi - row_lo <= 4 * kStagedChunk;     // wave-uniform
+        int row_base = 0, carried = 0;
+        if (staged) {
+            for (int i = lane; i <= len; i += kWave) cnt[i] = 0;
+            wave_lds_sync();
+            for (int r = row_lo + 1 + lane; r <= row_hi; r += kWave) atomicAdd(&cnt[rowptr[r] - c0], 1);
+            const int first_here = rowptr[row_lo] == c0 ? 1 : 0;
+            if (lane == 0) { cnt[0] = first_here; cnt[len] = rowptr[row_hi + 1] == c1 ? 1 : 0; }
+            wave_lds_sync();
+            row_base = row_lo - first_here;
+        }
         auto lookup = [&](int q) {
             int4 e = make_int4(0, 0, -1, 0);
-            if (q < c1) {
+            if (staged) {
+                const bool valid = q < c1;
+                const int here = valid ? cnt[q - c0] : 0, next = valid ? cnt[q - c0 + 1] : 0;
+                const int upto = wave_inclusive_scan_dpp(here);
+                if (valid) {
+                    e.x = colind[q];
+                    e.y = __float_as_int(vals[q]);
+                    e.z = row_base + carried + upto;
+                    e.w = (here > 0 ? 1 : 0) | (next > 0 ? 2 : 0);
+                }
+                carried += __builtin_amdgcn_readlane(upto, kWave - 1);
+            } else if (q < c1) {
                 const int r = row_of_entry(rowptr, row_lo, row_hi, q);
                 e.x = colind[q];
                 e.y = __float_as_int(vals[q]);
@@ -762,8 +855,8 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                     const int nv = min(S, cnt - t0);                   // valid slots in this step
                     const int first_row = __builtin_amdgcn_readfirstlane(er);
                     const int first_flags = __builtin_amdgcn_readfirstlane(e[u].w);
-                    const int last_row = __shfl(er, (nv - 1) * G, kWave);
-                    const int last_flags = __shfl(e[u].w, (nv - 1) * G, kWave);
+                    const int last_row = __builtin_amdgcn_readlane(er, (nv - 1) * G);
+                    const int last_flags = __builtin_amdgcn_readlane(e[u].w, (nv - 1) * G);
 
                     if (first_row == last_row) {
                         // one row in the whole step: no cross-lane work
@@ -779,10 +872,10 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                         // a row boundary inside the step: conditional reduction
                         const Acc<V, NV> p = b[u];                      // this slot's product
                         Acc<V, NV> x = p;
-                        // run heads: a slot whose left neighbour holds another row; the first
+                        // run heads: a slot whose entry is the first of its row (entries are stored
+                        // row after row, so its left neighbour then holds another row); the first
                         // slot past the valid ones counts as a head so that the last run ends there
-                        const int prow = __shfl_up(er, G, kWave);
-                        const bool head = s <= nv && (s == 0 || prow != er);
+                        const bool head = s <= nv && (s == 0 || s == nv || (e[u].w & 1) != 0);
                         const unsigned long long heads = __ballot(head);
                         // slots from s to the end of its run
                         int dist = S - 1 - s;
@@ -791,16 +884,9 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
                             if (above) dist = (__ffsll((long long)above) - 1) / G;
                         }
 #pragma unroll
-                        for (int d = 1; d < S; d <<= 1) {
-                            const bool take = d <= dist;
+                        for (int i = 0; i < NV; ++i)
 #pragma unroll
-                            for (int i = 0; i < NV; ++i)
-#pragma unroll
-                                for (int v = 0; v < V; ++v) {
-                                    const float ox = __shfl_down(x.a[i][v], d * G, kWave);
-                                    if (take) x.a[i][v] += ox;
-                                }
-                        }
+                            for (int v = 0; v < V; ++v) conditional_steps<G, 1>(x.a[i][v], dist);
                         // the run that starts the step continues the row accumulated so far
                         bool started = true;                            // runs that begin inside the step
                         if (cur >= 0) {

@@ -195,7 +195,8 @@ dev = torch.device("cuda:0")
 rp, ci, va, Bd = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals, B))
 for env, algos, ok in [(dict(G="8", PIN="1"), (0, 1, 4, 5), True), (dict(G="16", PIN="1", CHUNK="64"), (0, 4), True),
                        (dict(V="1", G="64"), (0, 4), True), (dict(NV="2"), (2, 3, 6, 7), True),
-                       (dict(G="3"), (0,), False), (dict(V="2"), (0,), False), (dict(G="32"), (1,), False)]:
+                       (dict(G="8"), (1, 5), True), (dict(G="16"), (1, 5), True), (dict(G="32"), (1, 5), True),
+                       (dict(G="3"), (0,), False), (dict(V="2"), (0,), False), (dict(G="64", V="1"), (1,), False)]:
     for k in ("V", "G", "NV", "CHUNK", "PIN"):
         os.environ.pop("DA_SPMM_" + k, None)
     for k, v in env.items():
@@ -210,6 +211,27 @@ for env, algos, ok in [(dict(G="8", PIN="1"), (0, 1, 4, 5), True), (dict(G="16",
             assert r <= 1.0, (env, algo, r)
         else:
             assert st == da.DA_ERR_UNSUPPORTED, (env, algo, st)
+# column tiles pinned to XCDs together with the chunk order of a prepared matrix (stripes dealt
+# to the XCDs that share a tile), on a matrix with enough chunks for several stripes
+a = gen.skewed_csr(m=20000, k=15000, heavy_frac=0.01, heavy_lo=4000, heavy_hi=9000, seed=12); N = 128
+B = gen.dense(a.k, N, "uniform", seed=7)
+c_ref, s_abs = orc.spmm(a.rowptr, a.colind, a.vals, B)
+rp, ci, va, Bd = (torch.from_numpy(x).to(dev) for x in (a.rowptr, a.colind, a.vals, B))
+da.da_spmm_features(a.m, N, rp)
+da.da_spmm_prepare(a.m, a.k, a.nnz, rp, ci)
+for env in (dict(G="16", PIN="1"), dict(G="8", PIN="1"), dict(G="16", PIN="1", CHUNK="64", STRIPE="16"), dict(G="4", PIN="1")):
+    for k in ("V", "G", "NV", "CHUNK", "PIN", "STRIPE"):
+        os.environ.pop("DA_SPMM_" + k, None)
+    for k, v in env.items():
+        os.environ["DA_SPMM_" + k] = v
+    for algo in (4, 5):
+        C = torch.full((a.m, N), float("nan"), device=dev)
+        st = da.da_spmm_status(a.m, a.k, N, rp, ci, va, Bd, C, algo)
+        torch.cuda.synchronize()
+        assert st == 0, (env, algo, st, da.da_spmm_last_error())
+        r = orc.tolerance_ratio(C.cpu().numpy(), c_ref, s_abs)
+        assert r <= 1.0, ("prepared", env, algo, r)
+da.da_spmm_release()
 print("overrides ok")
 """
     env = dict(os.environ, DA_SPMM_TUNE="1")
