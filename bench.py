@@ -70,11 +70,20 @@ def measured_traffic(workload: str, N: int, algo_name: str):
     if vals.get("ALGO") != algo_name:
         return None, None, f"counter summary under profiles/ is for {vals.get('ALGO')}"
     try:
-        total = int((float(vals["FETCH_KIB_PER_CALL_SCALED"]) + float(vals["WRITE_KIB_PER_CALL_SCALED"])) * 1024)
+        fetch = float(vals["FETCH_KIB_PER_CALL_SCALED"]) * 1024
+        total = int(fetch + float(vals["WRITE_KIB_PER_CALL_SCALED"]) * 1024)
         hit = float(vals["TCC_HIT_RATE"]) if vals.get("TCC_HIT_RATE", "n/a") != "n/a" else None
     except (KeyError, ValueError):
         return None, None, "counter summary under profiles/ is incomplete"
+    measured_traffic.fetch_bytes = fetch
     return total, hit, os.path.relpath(path, ROOT)
+
+
+measured_traffic.fetch_bytes = None
+
+# Rate at which this GPU serves 512-byte rows that miss the L2 caches (uniformly random rows of a
+# 134 MB table, stand-alone gather kernel `ceilings gather 128 262144 uniform`): 7.57 TB/s.
+RANDOM_ROW_MISS_TBPS = 7.57
 
 
 def stream_ceiling():
@@ -236,6 +245,10 @@ def main():
         "on_chip_gather_bound": {"bytes": 4 * a.nnz * N, "rate_TBps": 32.0,
                                  "us": round(4 * a.nnz * N / 32.0e6, 1),
                                  "frac_of_measured": round(4 * a.nnz * N / 32.0e6 / (ms * 1e3), 3)},
+        # what the memory system allows for the bytes this kernel fetches past the L2 caches: the
+        # measured fetch traffic over the rate at which rows that miss L2 can be served at all
+        "binding_bound_us": (None if measured_traffic.fetch_bytes is None else
+                             round(measured_traffic.fetch_bytes / (RANDOM_ROW_MISS_TBPS * 1e6), 1)),
         "features_ms_once_per_matrix": round(feat_ms, 3), "features_ms_first_call": round(feat_first_ms, 3),
         "select_us_per_call": round(select_us, 3),
         "prepare_ms_once_per_matrix": None if prep_ms is None else round(prep_ms, 3),

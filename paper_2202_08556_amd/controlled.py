@@ -59,6 +59,13 @@ def line(label, times, left, right, lname, rname):
 
 
 def main():
+    from .profile_summary import source_hash
+    print("Controlled experiments of the paper's Sec. 6.3 (Fig. 9) on seeded R-MAT matrices, one MI355X, fp32.")
+    print("command (repository root, after __graft_entry__.build()):  python -m paper_2202_08556_amd.controlled")
+    print(f"SOURCE_SHA256 = {source_hash()}")
+    print("HIP-event time per call (EB ids include the zero pre-pass), best id of each side of the axis; B and C rotate "
+          "over 3 copies.")
+    print("Matrices are prepared with da_spmm_prepare (EB chunk order) before timing.\n")
     print("RB-EB: R-MAT scale 17 (131072 rows), 16 entries per row on average, N = 32")
     for i, (a, b, c) in enumerate(((0.25, 0.25, 0.25), (0.45, 0.22, 0.22), (0.57, 0.19, 0.19))):
         m = gen.rmat_csr(17, 16.0, a, b, c, seed=8200 + i)

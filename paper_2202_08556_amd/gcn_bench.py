@@ -48,7 +48,14 @@ def main():
     ap.add_argument("--out", default=None)
     args = ap.parse_args()
     a = gen.powerlaw_csr(m=args.m, seed=args.seed)
-    lines = [f"power-law graph m=k={a.m} nnz={a.nnz} seed={args.seed} (values 1/row length: row-normalised adjacency)"]
+    from .profile_summary import source_hash
+    lines = ["GCN aggregation on the power-law graph: forward A.X, backward A^T.dY, all 8 ids vs the selector's choice,",
+             "one-off da_csr_transpose, two-layer GCN inference.  MI355X, HIP-event times (us); both matrices prepared",
+             "with da_spmm_prepare (EB chunk schedule).",
+             "command (repository root, after __graft_entry__.build()): python -m paper_2202_08556_amd.gcn_bench --out FILE",
+             f"SOURCE_SHA256 = {source_hash()}",
+             "ids in the last column, in order: " + " ".join(da.ALGO_NAMES),
+             f"power-law graph m=k={a.m} nnz={a.nnz} seed={args.seed} (values 1/row length: row-normalised adjacency)"]
     graph = gcn.SparseGraph.from_numpy(a)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -79,14 +79,14 @@ def predict(model, X):
     return np.array([walk(model, x) for x in X])
 
 
-def fit(X, T, Xval=None, Tval=None, n_trees=60, depth=5, lr=0.15, min_leaf=4, seed=0):
+def fit(X, T, Xval=None, Tval=None, n_trees=60, depth=5, lr=0.15, min_leaf=4, seed=0, slack=0.0):
     from sklearn.tree import DecisionTreeRegressor
     Y = np.log(T / T.min(axis=1, keepdims=True))          # log slow-down, >= 0
     Y = np.minimum(Y, np.log(50.0))                        # a 50x loss is as bad as it needs to be
     base = Y.mean(axis=0)
     trees = [dict(feature=[-1], threshold=[0.0], left=[0], right=[0], value=[(-base).tolist()])]
     F = np.tile(base, (len(X), 1))
-    best_model, best_score = None, -1.0
+    scores = []
     rng = np.random.RandomState(seed)
     for it in range(n_trees):
         reg = DecisionTreeRegressor(max_depth=depth, min_samples_leaf=min_leaf, random_state=rng.randint(1 << 30))
@@ -98,14 +98,13 @@ def fit(X, T, Xval=None, Tval=None, n_trees=60, depth=5, lr=0.15, min_leaf=4, se
                           left=[int(c) for c in tr.children_left], right=[int(c) for c in tr.children_right],
                           value=[(-lr * tr.value[i, :, 0]).tolist() for i in range(tr.node_count)]))
         if Xval is not None:
-            model = dict(trees=list(trees))
-            sc = normalized_performance(Tval, predict(model, Xval))
-            if sc > best_score + 1e-6:
-                best_score, best_model = sc, model
+            scores.append(normalized_performance(Tval, predict(dict(trees=trees), Xval)))
     if Xval is None:
         return dict(trees=trees)
-    best_model["validation_score"] = best_score
-    return best_model
+    # the smallest forest whose validation score is within `slack` of the best one: the last few
+    # thousandths cost most of the trees
+    keep = next(i for i, sc in enumerate(scores) if sc >= max(scores) - slack)
+    return dict(trees=trees[:keep + 2], validation_score=scores[keep])
 
 
 def write_inc(model, path, note):
@@ -155,6 +154,8 @@ def main():
     ap.add_argument("--trees", type=int, default=240)
     ap.add_argument("--depth", type=int, nargs="+", default=[4, 5, 6],
                     help="tree depths to try; the held-out tenth of the training sets picks one")
+    ap.add_argument("--slack", type=float, default=0.003,
+                    help="take the smallest forest whose validation score is within this of the best")
     ap.add_argument("--report", default=os.path.join(PKG, "selector_data", "report.txt"))
     ap.add_argument("--no-write", action="store_true")
     args = ap.parse_args()
@@ -168,8 +169,10 @@ def main():
     itr, iva, ite = perm[:n4], perm[n4:n5], perm[n5:]
     def fit_best(X, T, Xv, Tv):
         """One model per depth; the validation part picks the depth (and, inside fit, the number of trees)."""
-        models = [fit(X, T, Xv, Tv, n_trees=args.trees, depth=d) for d in args.depth]
-        best = max(range(len(models)), key=lambda i: models[i]["validation_score"])
+        models = [fit(X, T, Xv, Tv, n_trees=args.trees, depth=d, slack=args.slack) for d in args.depth]
+        top = max(mm["validation_score"] for mm in models)
+        best = min((i for i in range(len(models)) if models[i]["validation_score"] >= top - args.slack),
+                   key=lambda i: len(models[i]["trees"]))
         models[best]["depth"] = args.depth[best]
         return models[best]
 
