@@ -123,6 +123,7 @@ struct Plan {
     const void* colind = nullptr;
     int64_t m = 0, nnz = 0;
     int* order[4] = {nullptr, nullptr, nullptr, nullptr};
+    int* first_row[4] = {nullptr, nullptr, nullptr, nullptr};   // per schedule position: row of the chunk's first entry (hint)
     int units[4] = {0, 0, 0, 0};
     int first_units[4] = {0, 0, 0, 0};   // chunks of the first schedule segment (multi-row chunks)
     std::shared_ptr<DeviceBlock> block;
@@ -153,9 +154,9 @@ Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int 
                 if (kPlanUnits[i] == chunk) {
                     *keep = pl.block;
                     if (capturing) pl.captured = true;
-                    return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0, pl.first_units[i], 0, 0, 0, 3};
+                    return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0, pl.first_units[i], 0, 0, 0, 3, pl.first_row[i]};
                 }
-    return Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3};
+    return Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3, nullptr};
 }
 
 // Default geometry per algorithm family and N.  Measured on MI355X: 16-byte and 4-byte gathers
@@ -280,7 +281,7 @@ int launch_w(Family fam, const Problem& p, const Geometry& geo) {
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(p.stream, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
         Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0)
-                           ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3}
+                           ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3, nullptr}
                            : lookup_schedule(p.rowptr, p.colind, p.m, chunk, cap == hipStreamCaptureStatusActive, &keep);
         const int first_chunks = sch.split;
         sch.split = 0;
@@ -402,6 +403,9 @@ TransposePlan plan_transpose(int64_t k, int64_t nnz) {
     return t;
 }
 
+int enqueue_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
+                     int32_t* order, int32_t* first_segment, int32_t* first_rows, void* workspace, size_t workspace_bytes,
+                     void* stream);
 int check_transpose_args(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
                          const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals);
 int enqueue_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
@@ -703,6 +707,19 @@ int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t* bytes)
 int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
                    int32_t* order, int32_t* first_segment, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return enqueue_schedule(m, k, nnz, rowptr, colind, unit, order, first_segment, nullptr, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// da_eb_schedule; first_rows (device, may be null) also receives, in schedule order, the row of every
+// chunk's first entry: first_rows[u] belongs to chunk order[u]
+int enqueue_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
+                     int32_t* order, int32_t* first_segment, int32_t* first_rows, void* workspace, size_t workspace_bytes,
+                     void* stream)
+{
     if (m < 0 || k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
     if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
         return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
@@ -733,18 +750,25 @@ int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, con
     for (int p = 0; p < t.passes; ++p) {
         const int shift = p * t.digit_bits;
         const int in = p & 1, out = in ^ 1;
-        int* ids_out = p == t.passes - 1 ? order : ids[out];
+        const bool last = p == t.passes - 1;
+        int* ids_out = last ? order : ids[out];
+        // the last pass delivers the first rows of the chunks, in schedule order, where the caller wants them
+        float* pad_out = (last && first_rows) ? reinterpret_cast<float*>(first_rows) : pad[out];
         hipLaunchKernelGGL(radix_count_kernel, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys[in], n, shift, mask, hist, t.nblocks);
         hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
         hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(kSortBlock), 0, s, part, (int)t.parts);
         hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
         hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys[in], ids[in], pad[in], n,
-                           shift, mask, hist, t.nblocks, keys[out], ids_out, pad[out], (const int*)nullptr, 0);
+                           shift, mask, hist, t.nblocks, keys[out], ids_out, pad_out, (const int*)nullptr, 0);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "da_eb_schedule launch");
     return DA_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 int da_spmm_release(const int32_t* rowptr)
 {
@@ -780,7 +804,7 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
     size_t ints = 64, ws_bytes = 0;                        // the first 4 ints receive the segment sizes
     for (int i = 0; i < 4; ++i) {
         pl.units[i] = (int)((nnz + kPlanUnits[i] - 1) / kPlanUnits[i]);
-        ints += (size_t)((pl.units[i] + 63) & ~63);
+        ints += 2 * (size_t)((pl.units[i] + 63) & ~63);     // the order and the first rows of the chunks
         const size_t b = plan_transpose(2 * k, pl.units[i]).bytes;
         ws_bytes = b > ws_bytes ? b : ws_bytes;
     }
@@ -796,7 +820,10 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
     for (int i = 0; i < 4 && status == DA_OK; ++i) {
         pl.order[i] = seg + off;
         off += (size_t)((pl.units[i] + 63) & ~63);
-        status = da_eb_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], seg + i, ws.p, ws_bytes, stream);
+        pl.first_row[i] = seg + off;
+        off += (size_t)((pl.units[i] + 63) & ~63);
+        status = enqueue_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], seg + i, pl.first_row[i], ws.p,
+                                  ws_bytes, stream);
     }
     e = hipSuccess;
     if (status == DA_OK)

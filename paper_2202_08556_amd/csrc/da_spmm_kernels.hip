@@ -57,7 +57,23 @@ struct Schedule {
     int units;
     int nnz;
     int stripe, split, per_a, stripe_b, vblocks, nx_log2;
+    // first_row[u] (may be null): the row that owned the first entry of chunk order[u] when the
+    // order was built.  A hint only: a worker checks it against the row pointers it finds (two
+    // independent loads) and searches when it does not hold, so stale contents cost speed, never
+    // correctness.
+    const int* first_row;
 };
+
+// The row that owns stored entry q according to the hint r, or -1 when the hint does not hold.
+// *start / *end receive the row's pointers when it does.
+__device__ __forceinline__ int hinted_row(const int* __restrict__ rowptr, int m, int r, int q, int* start, int* end) {
+    if (r < 0 || r >= m) return -1;
+    const int a = rowptr[r], b = rowptr[r + 1];
+    if (a > q || q >= b) return -1;
+    *start = a;
+    *end = b;
+    return r;
+}
 
 // ------------------------------------------------------------------------------------------
 // small helpers
@@ -623,9 +639,16 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
         const long c0l = (scheduled ? (long)sch.order[u] : u) * chunk;
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);
-        int row = row_of_entry_group<G>(rowptr, 0, m - 1, c0, j, g * G);
-        int row_end = rowptr[row + 1];
-        bool shared_with_prev = rowptr[row] < c0;          // only the chunk's first row can be
+        // the chunk's first row: from the plan's hint when it holds (one round trip), else by the
+        // group's search (log_{G+1} m dependent loads)
+        int row_start = 0, row_end = 0;
+        int row = (scheduled && sch.first_row != nullptr) ? hinted_row(rowptr, m, sch.first_row[u], c0, &row_start, &row_end) : -1;
+        if (row < 0) {
+            row = row_of_entry_group<G>(rowptr, 0, m - 1, c0, j, g * G);
+            row_start = rowptr[row];
+            row_end = rowptr[row + 1];
+        }
+        bool shared_with_prev = row_start < c0;            // only the chunk's first row can be
         Acc<V, NV> acc;
         acc.clear();
 
@@ -770,7 +793,9 @@ __global__ __launch_bounds__(kBlock) void eb_pr_kernel(
         const long c0l = (scheduled ? (long)sch.order[u] : u) * chunk;
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);
-        const int row_lo = row_of_entry_group<kWave>(rowptr, 0, m - 1, c0, lane, 0);
+        int hint_start, hint_end;
+        int row_lo = (scheduled && sch.first_row != nullptr) ? hinted_row(rowptr, m, sch.first_row[u], c0, &hint_start, &hint_end) : -1;
+        if (row_lo < 0) row_lo = row_of_entry_group<kWave>(rowptr, 0, m - 1, c0, lane, 0);
         const int row_hi = row_of_entry_group<kWave>(rowptr, row_lo, m - 1, c1 - 1, lane, 0);
         Acc<V, NV> acc;                                    // per-slot partial sums of row `cur`
         acc.clear();

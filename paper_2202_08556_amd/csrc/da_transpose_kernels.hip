@@ -295,7 +295,8 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
 // are latency-bound where the single-row units are bandwidth-bound; a wave that holds both kinds
 // runs at the pace of the slower, so the kinds are kept apart, and the launch deals each segment
 // to all XCDs.  count (one int, cleared first) receives the number of units of that segment.
-// ids = 0, 1, 2, ...; pad = 0 (the value slot of the triples the radix passes move is not used).
+// ids = 0, 1, 2, ...; the value slot of the triples the radix passes move carries, as a bit pattern,
+// the row that owns the unit's first entry, so that the sort also delivers those rows in schedule order.
 __global__ void schedule_clear_kernel(int* __restrict__ count) { *count = 0; }
 
 __global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int m, int k, int nnz, const int* __restrict__ rowptr,
@@ -312,7 +313,7 @@ __global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int m, int k,
         several = rowptr[r0 + 1] <= c1;
         keys[u] = several ? colind[c0] : k + (int)(((long)colind[c0] + (long)colind[c1]) >> 1);
         ids[u] = (int)u;
-        pad[u] = 0.f;
+        pad[u] = __int_as_float(r0);
     }
     const unsigned long long vote = __ballot(several);
     if ((threadIdx.x & 63) == 0 && vote) atomicAdd(count, __popcll(vote));
