@@ -124,6 +124,7 @@ struct Plan {
     int64_t m = 0, nnz = 0;
     int* order[4] = {nullptr, nullptr, nullptr, nullptr};
     int* first_row[4] = {nullptr, nullptr, nullptr, nullptr};   // per schedule position: row of the chunk's first entry (hint)
+    int* row_by_chunk[4] = {nullptr, nullptr, nullptr, nullptr}; // the same rows indexed by chunk number
     int units[4] = {0, 0, 0, 0};
     int first_units[4] = {0, 0, 0, 0};   // chunks of the first schedule segment (multi-row chunks)
     std::shared_ptr<DeviceBlock> block;
@@ -154,9 +155,9 @@ Schedule lookup_schedule(const void* rowptr, const void* colind, int64_t m, int 
                 if (kPlanUnits[i] == chunk) {
                     *keep = pl.block;
                     if (capturing) pl.captured = true;
-                    return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0, pl.first_units[i], 0, 0, 0, 3, pl.first_row[i]};
+                    return Schedule{pl.order[i], pl.units[i], (int)pl.nnz, 0, pl.first_units[i], 0, 0, 0, 3, pl.first_row[i], pl.row_by_chunk[i]};
                 }
-    return Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3, nullptr};
+    return Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3, nullptr, nullptr};
 }
 
 // Default geometry per algorithm family and N.  Measured on MI355X: 16-byte and 4-byte gathers
@@ -273,16 +274,20 @@ int launch_w(Family fam, const Problem& p, const Geometry& geo) {
             if (blocks > full) blocks = full;
         }
         if (blocks < 1) blocks = 1;
-        // pre-pass: zero the rows that receive atomic additions, and the rows without entries
-        const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
-        hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.C, chunk);
         // chunk order of a prepared matrix (column sweep), if one exists for this chunk size
         std::shared_ptr<DeviceBlock> keep;                 // dropped after the launch
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(p.stream, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
         Schedule sch = env_int("DA_SPMM_NO_SCHEDULE", 0)
-                           ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3, nullptr}
+                           ? Schedule{nullptr, 0, 0, 0, 0, 0, 0, 0, 3, nullptr, nullptr}
                            : lookup_schedule(p.rowptr, p.colind, p.m, chunk, cap == hipStreamCaptureStatusActive, &keep);
+        // EB+SR on a prepared matrix never splits rows of at most a chunk (the plan's row hints make
+        // the second boundary look-up cheap); the zero pass and the product kernel are told alike
+        const int own_short = (fam == EB_SR && kOwnShortRows<G> && sch.order != nullptr &&
+                               env_int("DA_SPMM_SPLIT_SHORT_ROWS", 0) == 0) ? 1 : 0;
+        // pre-pass: zero the rows that receive atomic additions, and the rows without entries
+        const dim3 zgrid((unsigned)((p.m + kBlock - 1) / kBlock));
+        hipLaunchKernelGGL((eb_zero_kernel<V>), zgrid, block, 0, p.stream, p.m, p.N, p.sd, p.rowptr, p.C, chunk, own_short);
         const int first_chunks = sch.split;
         sch.split = 0;
         if (sch.order && geo.stripe > 0) {
@@ -317,7 +322,7 @@ int launch_w(Family fam, const Problem& p, const Geometry& geo) {
         }
         if (fam == EB_SR) {
             hipLaunchKernelGGL((eb_sr_kernel<V, G, NV, WIDE>), grid_for(blocks), block, 0, p.stream,
-                               p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin, sch);
+                               p.m, p.N, p.sd, p.rowptr, p.colind, p.vals, p.B, p.C, chunk, pin, sch, own_short);
         } else {
             if constexpr (G <= kMaxGroupPR)
                 hipLaunchKernelGGL((eb_pr_kernel<V, G, NV, WIDE>), grid_for(blocks), block, 0, p.stream,
@@ -404,8 +409,8 @@ TransposePlan plan_transpose(int64_t k, int64_t nnz) {
 }
 
 int enqueue_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
-                     int32_t* order, int32_t* first_segment, int32_t* first_rows, void* workspace, size_t workspace_bytes,
-                     void* stream);
+                     int32_t* order, int32_t* first_segment, int32_t* first_rows, int32_t* rows_by_unit, void* workspace,
+                     size_t workspace_bytes, void* stream);
 int check_transpose_args(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
                          const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals);
 int enqueue_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
@@ -707,7 +712,8 @@ int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t* bytes)
 int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
                    int32_t* order, int32_t* first_segment, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return enqueue_schedule(m, k, nnz, rowptr, colind, unit, order, first_segment, nullptr, workspace, workspace_bytes, stream);
+    return enqueue_schedule(m, k, nnz, rowptr, colind, unit, order, first_segment, nullptr, nullptr, workspace, workspace_bytes,
+                            stream);
 }
 
 }  // extern "C"
@@ -715,10 +721,11 @@ int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, con
 namespace {
 
 // da_eb_schedule; first_rows (device, may be null) also receives, in schedule order, the row of every
-// chunk's first entry: first_rows[u] belongs to chunk order[u]
+// chunk's first entry: first_rows[u] belongs to chunk order[u]; rows_by_unit (device, may be null) the same
+// rows indexed by chunk number
 int enqueue_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
-                     int32_t* order, int32_t* first_segment, int32_t* first_rows, void* workspace, size_t workspace_bytes,
-                     void* stream)
+                     int32_t* order, int32_t* first_segment, int32_t* first_rows, int32_t* rows_by_unit, void* workspace,
+                     size_t workspace_bytes, void* stream)
 {
     if (m < 0 || k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
     if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
@@ -745,7 +752,7 @@ int enqueue_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, c
     int* count = first_segment ? first_segment : part;  // part is free until the first scan
     hipLaunchKernelGGL(schedule_clear_kernel, dim3(1), dim3(1), 0, s, count);
     hipLaunchKernelGGL(schedule_keys_kernel, kgrid, dim3(kSortBlock), 0, s, (int)m, (int)k, (int)nnz, rowptr, colind,
-                       unit, n, keys[0], ids[0], pad[0], count);
+                       unit, n, keys[0], ids[0], pad[0], count, rows_by_unit);
     const int mask = (1 << t.digit_bits) - 1;
     for (int p = 0; p < t.passes; ++p) {
         const int shift = p * t.digit_bits;
@@ -804,7 +811,7 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
     size_t ints = 64, ws_bytes = 0;                        // the first 4 ints receive the segment sizes
     for (int i = 0; i < 4; ++i) {
         pl.units[i] = (int)((nnz + kPlanUnits[i] - 1) / kPlanUnits[i]);
-        ints += 2 * (size_t)((pl.units[i] + 63) & ~63);     // the order and the first rows of the chunks
+        ints += 3 * (size_t)((pl.units[i] + 63) & ~63);     // the order and, twice, the first rows of the chunks
         const size_t b = plan_transpose(2 * k, pl.units[i]).bytes;
         ws_bytes = b > ws_bytes ? b : ws_bytes;
     }
@@ -822,8 +829,10 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
         off += (size_t)((pl.units[i] + 63) & ~63);
         pl.first_row[i] = seg + off;
         off += (size_t)((pl.units[i] + 63) & ~63);
-        status = enqueue_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], seg + i, pl.first_row[i], ws.p,
-                                  ws_bytes, stream);
+        pl.row_by_chunk[i] = seg + off;
+        off += (size_t)((pl.units[i] + 63) & ~63);
+        status = enqueue_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], seg + i, pl.first_row[i],
+                                  pl.row_by_chunk[i], ws.p, ws_bytes, stream);
     }
     e = hipSuccess;
     if (status == DA_OK)

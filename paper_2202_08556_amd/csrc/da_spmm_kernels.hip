@@ -62,6 +62,9 @@ struct Schedule {
     // independent loads) and searches when it does not hold, so stale contents cost speed, never
     // correctness.
     const int* first_row;
+    // row_by_chunk[c] (may be null): the same hint indexed by chunk number; a worker on chunk c
+    // reads row_by_chunk[c + 1], the row at the boundary that follows its chunk
+    const int* row_by_chunk;
 };
 
 // The row that owns stored entry q according to the hint r, or -1 when the hint does not hold.
@@ -371,12 +374,12 @@ __device__ __forceinline__ long sweep_block(long vb, const Schedule& sch) {
     return sch.split + (long)(t * nx + x) * st + (l - t * st);
 }
 
-// Calls f(Count<UU>, t) for t covering [0, cnt) in blocks of UMAX, then 8, 4, 2, 1 entries, so that
+// Calls f(Count<UU>, t) for t covering [begin, cnt) in blocks of UMAX, then 8, 4, 2, 1 entries, so that
 // every block is straight-line code of a compile-time size: its gathers carry no predicates and
 // are all in flight before the first one is consumed.
 template <int UMAX, class F>
-__device__ __forceinline__ void for_blocks(int cnt, F&& f) {
-    int t = 0;
+__device__ __forceinline__ void for_blocks(int begin, int cnt, F&& f) {
+    int t = begin;
     for (; t + UMAX <= cnt; t += UMAX) f(Count<UMAX>{}, t);
     static_assert(UMAX <= 16, "the remainder is covered by blocks of 8, 4, 2, 1");
     if constexpr (UMAX > 8) { if (t + 8 <= cnt) { f(Count<8>{}, t); t += 8; } }
@@ -384,6 +387,8 @@ __device__ __forceinline__ void for_blocks(int cnt, F&& f) {
     if constexpr (UMAX > 2) { if (t + 2 <= cnt) { f(Count<2>{}, t); t += 2; } }
     if constexpr (UMAX > 1) { if (t < cnt) f(Count<1>{}, t); }
 }
+template <int UMAX, class F>
+__device__ __forceinline__ void for_blocks(int cnt, F&& f) { for_blocks<UMAX>(0, cnt, f); }
 
 // ------------------------------------------------------------------------------------------
 // RB + SR : a lane group owns a row and adds its products one after another
@@ -552,13 +557,14 @@ __global__ __launch_bounds__(kBlock) void rb_pr_kernel(
 // store; a row that straddles a chunk boundary receives atomic additions from several workers and
 // must start from zero; a row without entries is touched by no worker.  This pass zeroes exactly
 // those two kinds of rows so that C needs no full memset.  `chunk` is the number of entries per
-// worker of the product kernel that follows.  A wave inspects 64 rows (one per lane) and then
+// worker of the product kernel that follows.  own_short: that kernel gives every row of at most
+// `chunk` entries to a single worker (see eb_sr_kernel), so only longer rows are shared.  A wave inspects 64 rows (one per lane) and then
 // clears the flagged ones together: one row at a time with full-width stores when a row takes
 // more than 32 stores, several rows per store instruction otherwise.
 // ------------------------------------------------------------------------------------------
 template <int V>
 __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
-    int m, int N, Strides sd, const int* __restrict__ rowptr, float* __restrict__ C, int chunk)
+    int m, int N, Strides sd, const int* __restrict__ rowptr, float* __restrict__ C, int chunk, int own_short)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const long base = ((long)blockIdx.x * kWavesPerBlock + wave) * kWave;
@@ -567,7 +573,7 @@ __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
     bool need = false;
     if (row < m) {
         const int start = rowptr[row], end = rowptr[row + 1];
-        need = (end == start) || (start / chunk != (end - 1) / chunk);
+        need = (end == start) || (start / chunk != (end - 1) / chunk && (!own_short || end - start > chunk));
     }
     unsigned long long mask = __ballot(need);
     float z[V];
@@ -605,13 +611,20 @@ __global__ __launch_bounds__(kBlock) void eb_zero_kernel(
 // neighbouring chunk (the "partial sum aggregation among workers" of Sec. 3.2).  The row of the
 // chunk's first entry is found by binary search in rowptr (the "row index calculation" overhead
 // named there).  Workers stride over the chunks so that the grid size does not depend on nnz,
-// which only the device knows.
+// which only the device knows.  With own_short the chunk boundaries give way to short rows: a row
+// of at most `chunk` entries that straddles a boundary goes whole to the worker in whose chunk it
+// starts, so that only rows longer than a chunk take atomic additions (eb_zero_kernel is told).
 // ------------------------------------------------------------------------------------------
+// Lane groups for which EB+SR can keep short rows whole (own_short): measured to pay for groups of
+// 16 and 32 lanes (power-law N = 128 468 -> 460 us); for groups of 8 the extra bookkeeping costs
+// registers and occupancy (power-law N = 32 144 -> 148 us), so those kernels are built without it.
+template <int G> constexpr bool kOwnShortRows = G >= 16;
+
 template <int V, int G, int NV, bool WIDE>
 __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
     int m, int N, Strides sd, const int* __restrict__ rowptr, const int* __restrict__ colind,
     const float* __restrict__ vals, const float* __restrict__ B, float* __restrict__ C, int chunk,
-    int pin_tiles, Schedule sch)
+    int pin_tiles, Schedule sch, int own_short)
 {
     constexpr int GPW = kWave / G;                        // workers per wave
     constexpr int SB = StageBatch<G>::value;
@@ -636,7 +649,8 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
         const long sb = striped ? sweep_block(vb, sch) : vb;
         const long u = sb * WPB + wave * GPW + g;
         if (sb < 0 || u >= nunits) continue;
-        const long c0l = (scheduled ? (long)sch.order[u] : u) * chunk;
+        const long cid = scheduled ? (long)sch.order[u] : u;
+        const long c0l = cid * chunk;
         const int c0 = (int)c0l;
         const int c1 = (int)min(c0l + chunk, (long)nnz);
         // the chunk's first row: from the plan's hint when it holds (one round trip), else by the
@@ -648,19 +662,58 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
             row_start = rowptr[row];
             row_end = rowptr[row + 1];
         }
-        bool shared_with_prev = row_start < c0;            // only the chunk's first row can be
+        BatchRegs<G, SB> next;
+        // the first batch is fetched before the worker knows where exactly its entries begin and end
+        if constexpr (G > 1) next.fetch(colind, vals, c0, (int)min(c0l + 2l * chunk, (long)nnz), j);
+        // Rows of at most `chunk` entries are never split (own_short): the one that straddles the
+        // chunk's end is finished by this worker, the one that straddles its start was finished by
+        // the worker before.  Both workers read the same row pointers, so they agree; a worker then
+        // owns the entries [lo, hi), between 0 and 2 * chunk - 1 of them, and only rows longer than a
+        // chunk are combined with atomic additions.
+        int lo = c0, hi = c1;
+        if (kOwnShortRows<G> && own_short) {
+            if (c1 < nnz) {
+                int bs = 0, be = 0;
+                int rb = (scheduled && sch.row_by_chunk != nullptr)
+                             ? hinted_row(rowptr, m, sch.row_by_chunk[cid + 1], c1, &bs, &be) : -1;
+                if (rb < 0) {
+                    rb = row_of_entry_group<G>(rowptr, row, m - 1, c1, j, g * G);
+                    bs = rowptr[rb];
+                    be = rowptr[rb + 1];
+                }
+                if (bs < c1 && be - bs <= chunk) hi = be;
+            }
+            if (row_start < c0 && row_end - row_start <= chunk) {
+                lo = row_end;
+                if (lo < hi) {                                 // the next row with entries starts at lo
+                    int walked = 0;
+                    do { ++row; row_end = rowptr[row + 1]; } while (row_end <= lo && ++walked < 4);
+                    if (row_end <= lo) {
+                        row = row_of_entry_group<G>(rowptr, row + 1, m - 1, lo, j, g * G);
+                        row_end = rowptr[row + 1];
+                    }
+                    row_start = lo;
+                }
+            }
+        }
+        if (lo >= hi) continue;
+        bool shared_with_prev = row_start < lo;            // only the worker's first row can be
         Acc<V, NV> acc;
         acc.clear();
 
-        BatchRegs<G, SB> next;
-        if constexpr (G > 1) next.fetch(colind, vals, c0, c1, j);
-        for (int q0 = c0; q0 < c1; q0 += SB) {
+        int q0 = c0, skip = lo - c0;                       // entries of the first batch that are not ours
+        if (skip >= SB) {                                  // the first batch holds none of ours: fetch again
+            q0 = lo;
+            skip = 0;
+            if constexpr (G > 1) next.fetch(colind, vals, q0, hi, j);
+        }
+        for (; q0 < hi; q0 += SB, skip = 0) {
             if constexpr (G > 1) {
                 next.put(st, j);
                 wave_lds_sync();
-                if (q0 + SB < c1) next.fetch(colind, vals, q0 + SB, c1, j);
+                if (q0 + SB < hi) next.fetch(colind, vals, q0 + SB, hi, j);
             }
-            for_blocks<UL>(min(SB, c1 - q0), [&](auto uc, int t) {
+            for_blocks<UL>(skip, min(SB, hi - q0), [&](auto uc, int t) {
                 constexpr int UU = decltype(uc)::value;
                 int2 e[UU];
                 Acc<V, NV> b[UU];
@@ -696,7 +749,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
                             if (nvec > 0) acc.emit(Cn + (long)row * sd.rc, nvec, shared_with_prev, sd.cc);
                             acc.clear();
                             shared_with_prev = false;
-                            if (next < c1) {
+                            if (next < hi) {
                                 // the next row with entries: usually row + 1; after a few rows
                                 // without entries search instead of walking (a run of thousands
                                 // of empty rows would otherwise cost a dependent load each)
@@ -713,7 +766,7 @@ __global__ __launch_bounds__(kBlock) void eb_sr_kernel(
             });
             if constexpr (G > 1) wave_lds_sync();
         }
-        if (row_end > c1 && nvec > 0)                      // last row continues in the next chunk
+        if (row_end > hi && nvec > 0)                      // last row continues with the next worker
             acc.emit(Cn + (long)row * sd.rc, nvec, true, sd.cc);
     }
 }

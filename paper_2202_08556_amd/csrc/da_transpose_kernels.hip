@@ -296,13 +296,15 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
 // runs at the pace of the slower, so the kinds are kept apart, and the launch deals each segment
 // to all XCDs.  count (one int, cleared first) receives the number of units of that segment.
 // ids = 0, 1, 2, ...; the value slot of the triples the radix passes move carries, as a bit pattern,
-// the row that owns the unit's first entry, so that the sort also delivers those rows in schedule order.
+// the row that owns the unit's first entry, so that the sort also delivers those rows in schedule order;
+// rows_by_unit (may be null) receives the same rows indexed by unit number.
 __global__ void schedule_clear_kernel(int* __restrict__ count) { *count = 0; }
 
 __global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int m, int k, int nnz, const int* __restrict__ rowptr,
                                                                    const int* __restrict__ colind, int unit, int nunits,
                                                                    int* __restrict__ keys, int* __restrict__ ids,
-                                                                   float* __restrict__ pad, int* __restrict__ count)
+                                                                   float* __restrict__ pad, int* __restrict__ count,
+                                                                   int* __restrict__ rows_by_unit)
 {
     const long u = (long)blockIdx.x * kSortBlock + threadIdx.x;
     bool several = false;
@@ -314,6 +316,7 @@ __global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int m, int k,
         keys[u] = several ? colind[c0] : k + (int)(((long)colind[c0] + (long)colind[c1]) >> 1);
         ids[u] = (int)u;
         pad[u] = __int_as_float(r0);
+        if (rows_by_unit) rows_by_unit[u] = r0;
     }
     const unsigned long long vote = __ballot(several);
     if ((threadIdx.x & 63) == 0 && vote) atomicAdd(count, __popcll(vote));
