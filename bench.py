@@ -121,6 +121,8 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="input/output copies rotated between steps")
     ap.add_argument("--no-variants", action="store_true", help="skip timing each of the 8 ids")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-unprepared", action="store_true",
+                    help="skip the extra timing of unprepared matrices (profiling runs: keeps the kernel's calls uniform)")
     ap.add_argument("--no-prepare", action="store_true",
                     help="skip da_spmm_prepare (the one-off per-matrix chunk schedule of the EB algorithms)")
     args = ap.parse_args()
@@ -281,7 +283,7 @@ def main():
         log(f"graph capture skipped: {exc}")
     # the same call on matrices that were never prepared (no chunk order): what a caller gets who
     # skips the once-per-matrix da_spmm_prepare
-    if not args.no_prepare:
+    if not args.no_prepare and not args.no_unprepared:
         da.da_spmm_release()
         out["unprepared_ms"] = round(timed(max(5, args.steps // 4), 3), 6)
     out["stream_ceiling"] = stream_ceiling()

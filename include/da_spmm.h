@@ -23,6 +23,7 @@
  *   DA_SPMM_DEBUG_VALIDATE=1   check the CSR arrays on the device before every product / transpose
  *   DA_SPMM_NO_SCHEDULE=1      ignore the chunk orders of prepared matrices (da_spmm_prepare)
  *   DA_SPMM_NO_SPLIT=1         deal such an order to the XCDs as one segment instead of two
+ *   DA_SPMM_SPLIT_SHORT_ROWS=1 EB+SR on prepared matrices: split short rows at chunk boundaries again
  *   DA_SPMM_WIDE=1             force the kernels with 64-bit gather addresses
  *   DA_SPMM_TUNE=1             honour DA_SPMM_V / _G / _NV / _CHUNK / _PIN / _STRIPE, which override the
  *                              launch geometry; unsupported combinations return DA_ERR_UNSUPPORTED
@@ -147,8 +148,10 @@ int da_spmm_features(int64_t m, int64_t N, const int32_t *rowptr, void *stream, 
  * gather of B into a sweep from low to high rows: concurrently running workers share a narrow
  * band of B that stays in the L2 caches.
  *
- * da_spmm_prepare builds those orders for the chunk sizes the EB kernels use and keeps them, keyed
- * by (rowptr, colind, m), in library-owned device memory (about nnz/34 ints) until da_spmm_release
+ * da_spmm_prepare builds those orders for the chunk sizes the EB kernels use, together with the row
+ * that owns each chunk's first entry (a hint the kernels check against the row pointers before they
+ * use it), and keeps them, keyed by (rowptr, colind, m), in library-owned device memory (about
+ * nnz/11 ints) until da_spmm_release
  * (rowptr == NULL releases every matrix) or until 16 other matrices have been prepared.  Later
  * da_spmm / da_spmm_ex calls with the same rowptr, colind and m and an EB algorithm id pick the
  * order up by themselves; results are the same up to fp32 rounding order.  It also records nnz

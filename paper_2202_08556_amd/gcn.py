@@ -19,7 +19,12 @@ from . import binding as da
 
 class SparseGraph:
     """CSR matrix A (m x k) resident on the device, with its selector features, the algorithm
-    chosen per feature length, and (built on first use) A^T."""
+    chosen per feature length, and (built on first use) A^T.
+
+    The first product prepares the matrix (da_spmm_prepare: EB chunk order and row hints).  The
+    library keeps the plans of the 16 most recently prepared matrices; a program that holds more
+    graphs than that (a graph and its transpose count as two) loses the oldest plans silently, which
+    costs the EB algorithms their chunk order (speed), never the result."""
 
     def __init__(self, m: int, k: int, rowptr: torch.Tensor, colind: torch.Tensor, vals: torch.Tensor):
         if rowptr.dtype != torch.int32 or colind.dtype != torch.int32 or vals.dtype != torch.float32:

@@ -234,6 +234,22 @@ def test_eb_schedule_has_the_promised_properties(a, units):
     assert da.da_eb_schedule_status(a.m, a.k, nnz, None, ci, 64, order, None, ws, nbytes) == da.DA_ERR_INVALID_ARG
 
 
+def rows_around_the_chunk_size(seed=71):
+    """Row lengths at and around the EB+SR chunk sizes (128, 256), rows that begin or end exactly
+    on chunk boundaries, runs of rows without entries and single-entry rows in between: the shapes
+    the rule "rows of at most a chunk are never split" has to get right."""
+    rng = np.random.default_rng(seed)
+    menu = np.array([0, 0, 1, 2, 127, 128, 129, 255, 256, 257, 300, 511, 512, 513, 1024, 33, 64])
+    lens = rng.choice(menu, size=1500)
+    lens[:8] = [256, 256, 128, 128, 0, 256, 255, 1]                 # boundaries that fall on row starts
+    lens[100:140] = 0                                               # a run of rows without entries
+    k = 6000
+    rowptr, colind = gen.csr_from_lens(rng, lens, k)
+    vals = rng.uniform(-1, 1, size=colind.size).astype(np.float32)
+    return gen.CSR(m=len(lens), k=k, rowptr=rowptr.astype(np.int32), colind=colind.astype(np.int32), vals=vals,
+                   seed=seed, name="rows_around_chunk")
+
+
 PREPARED = [("skewed", lambda: gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9000, seed=4001), [8, 64]),
             ("powerlaw", lambda: gen.powerlaw_csr(m=8192, seed=2001), [32, 128]),
             ("one_long_row", lambda: gen.skewed_csr(m=64, k=40000, heavy_frac=0.02, heavy_lo=30000, heavy_hi=30000,
@@ -242,7 +258,10 @@ PREPARED = [("skewed", lambda: gen.skewed_csr(m=16384, heavy_lo=3000, heavy_hi=9
             # chunks for several rounds of XCD stripes at the smallest chunk size
             ("wide_and_ragged_N", lambda: gen.skewed_csr(m=20000, k=15000, heavy_frac=0.01, heavy_lo=4000,
                                                          heavy_hi=9000, seed=12), [520, 13]),
-            ("few_entries", lambda: gen.uniform_csr(m=9, k=11, mean_len=3, seed=5), [4])]
+            ("few_entries", lambda: gen.uniform_csr(m=9, k=11, mean_len=3, seed=5), [4]),
+            # lane groups of 32 / 16 (rows of at most a chunk stay whole) and of 8 (they are split)
+            ("rows_around_chunk", rows_around_the_chunk_size, [128, 64, 32]),
+            ("hypersparse", lambda: gen.hypersparse_csr(200000, 25000, 0.01, 100.0, seed=73), [128])]
 
 
 @pytest.mark.parametrize("name,make,Ns", PREPARED, ids=[p[0] for p in PREPARED])
