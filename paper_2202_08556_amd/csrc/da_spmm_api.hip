@@ -408,9 +408,16 @@ TransposePlan plan_transpose(int64_t k, int64_t nnz) {
     return t;
 }
 
-int enqueue_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
-                     int32_t* order, int32_t* first_segment, int32_t* first_rows, int32_t* rows_by_unit, void* workspace,
-                     size_t workspace_bytes, void* stream);
+// One schedule to build: da_eb_schedule's outputs, and optionally the row of every chunk's first
+// entry in schedule order (first_rows[u] belongs to chunk order[u]) and indexed by chunk number
+// (rows_by_unit); all device pointers, the last three may be null
+struct ScheduleJob {
+    int unit;
+    int32_t* order; int32_t* first_segment; int32_t* first_rows; int32_t* rows_by_unit;
+    void* workspace; size_t workspace_bytes;
+};
+int enqueue_schedules(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                      const ScheduleJob* jobs, int njobs, void* stream);
 int check_transpose_args(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
                          const float* vals, int32_t* t_rowptr, int32_t* t_colind, float* t_vals);
 int enqueue_transpose(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
@@ -712,61 +719,89 @@ int da_eb_schedule_workspace(int64_t k, int64_t nnz, int unit, size_t* bytes)
 int da_eb_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
                    int32_t* order, int32_t* first_segment, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return enqueue_schedule(m, k, nnz, rowptr, colind, unit, order, first_segment, nullptr, nullptr, workspace, workspace_bytes,
-                            stream);
+    const ScheduleJob job{unit, order, first_segment, nullptr, nullptr, workspace, workspace_bytes};
+    return enqueue_schedules(m, k, nnz, rowptr, colind, &job, 1, stream);
 }
 
 }  // extern "C"
 
 namespace {
 
-// da_eb_schedule; first_rows (device, may be null) also receives, in schedule order, the row of every
-// chunk's first entry: first_rows[u] belongs to chunk order[u]; rows_by_unit (device, may be null) the same
-// rows indexed by chunk number
-int enqueue_schedule(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind, int unit,
-                     int32_t* order, int32_t* first_segment, int32_t* first_rows, int32_t* rows_by_unit, void* workspace,
-                     size_t workspace_bytes, void* stream)
+// Builds up to kMaxSortJobs schedules of one matrix side by side: every stage is one launch whose
+// blockIdx.y selects the schedule, so four chunk sizes cost the launches of one.  The number of
+// radix passes depends on k alone and is therefore the same for every job.
+int enqueue_schedules(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                      const ScheduleJob* jobs, int njobs, void* stream)
 {
-    if (m < 0 || k < 0 || nnz < 0 || unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
+    if (m < 0 || k < 0 || nnz < 0) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
     if (m > 0x7ffffffeLL || k > 0x7ffffffeLL || nnz > 0x7fffffffLL)
         return fail(DA_ERR_INVALID_ARG, "size beyond the int32 index range%s");
     if (k > (1LL << 30)) return fail(DA_ERR_UNSUPPORTED, "more than 2^30 columns%s");
+    if (njobs < 1 || njobs > kMaxSortJobs) return fail(DA_ERR_INVALID_ARG, "number of schedules out of range%s");
+    for (int i = 0; i < njobs; ++i)
+        if (jobs[i].unit < 1) return fail(DA_ERR_INVALID_ARG, "negative size or unit < 1%s");
     if (nnz == 0) return DA_OK;
     if (m == 0) return fail(DA_ERR_INVALID_ARG, "stored entries in a matrix without rows%s");
-    if (!rowptr || !colind || !order) return fail(DA_ERR_INVALID_ARG, "null rowptr, colind or order%s");
-    const int64_t nunits = (nnz + unit - 1) / unit;
-    const TransposePlan t = plan_transpose(2 * k, nunits);
-    if (!workspace || workspace_bytes < t.bytes)
-        return fail(DA_ERR_INVALID_ARG, "workspace missing or smaller than da_eb_schedule_workspace reports%s");
-    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
-        return fail(DA_ERR_INVALID_ARG, "workspace is not 256-byte aligned%s");
+    if (!rowptr || !colind) return fail(DA_ERR_INVALID_ARG, "null rowptr, colind or order%s");
+    TransposePlan t[kMaxSortJobs];
+    int n[kMaxSortJobs];
+    int *keys[kMaxSortJobs][2], *ids[kMaxSortJobs][2];
+    float* pad[kMaxSortJobs][2];
+    KeyJobs kj{};
+    unsigned max_units_blocks = 0, max_nblocks = 0, max_parts = 0;
+    for (int i = 0; i < njobs; ++i) {
+        const ScheduleJob& J = jobs[i];
+        if (!J.order) return fail(DA_ERR_INVALID_ARG, "null rowptr, colind or order%s");
+        const int64_t nunits = (nnz + J.unit - 1) / J.unit;
+        t[i] = plan_transpose(2 * k, nunits);
+        if (!J.workspace || J.workspace_bytes < t[i].bytes)
+            return fail(DA_ERR_INVALID_ARG, "workspace missing or smaller than da_eb_schedule_workspace reports%s");
+        if (reinterpret_cast<uintptr_t>(J.workspace) % 256 != 0)
+            return fail(DA_ERR_INVALID_ARG, "workspace is not 256-byte aligned%s");
+        char* ws = static_cast<char*>(J.workspace);
+        for (int b = 0; b < 2; ++b) {
+            keys[i][b] = reinterpret_cast<int*>(ws + t[i].off_keys[b]);
+            ids[i][b] = reinterpret_cast<int*>(ws + t[i].off_rows[b]);
+            pad[i][b] = reinterpret_cast<float*>(ws + t[i].off_vals[b]);
+        }
+        n[i] = (int)nunits;
+        int* part = reinterpret_cast<int*>(ws + t[i].off_part);
+        // without a caller's counter the chunk sums serve: they are free until the first scan
+        kj.j[i] = KeyJob{J.unit, n[i], keys[i][0], ids[i][0], pad[i][0], J.first_segment ? J.first_segment : part, J.rows_by_unit};
+        const unsigned ub = (unsigned)((n[i] + kSortBlock - 1) / kSortBlock);
+        max_units_blocks = ub > max_units_blocks ? ub : max_units_blocks;
+        max_nblocks = (unsigned)t[i].nblocks > max_nblocks ? (unsigned)t[i].nblocks : max_nblocks;
+        max_parts = (unsigned)t[i].parts > max_parts ? (unsigned)t[i].parts : max_parts;
+    }
     hipStream_t s = (hipStream_t)stream;
-    char* ws = static_cast<char*>(workspace);
-    int* keys[2] = {reinterpret_cast<int*>(ws + t.off_keys[0]), reinterpret_cast<int*>(ws + t.off_keys[1])};
-    int* ids[2] = {reinterpret_cast<int*>(ws + t.off_rows[0]), reinterpret_cast<int*>(ws + t.off_rows[1])};
-    float* pad[2] = {reinterpret_cast<float*>(ws + t.off_vals[0]), reinterpret_cast<float*>(ws + t.off_vals[1])};
-    int* hist = reinterpret_cast<int*>(ws + t.off_hist);
-    int* part = reinterpret_cast<int*>(ws + t.off_part);
-    const int n = (int)nunits;
-    const dim3 kgrid((unsigned)((n + kSortBlock - 1) / kSortBlock));
-    int* count = first_segment ? first_segment : part;  // part is free until the first scan
-    hipLaunchKernelGGL(schedule_clear_kernel, dim3(1), dim3(1), 0, s, count);
-    hipLaunchKernelGGL(schedule_keys_kernel, kgrid, dim3(kSortBlock), 0, s, (int)m, (int)k, (int)nnz, rowptr, colind,
-                       unit, n, keys[0], ids[0], pad[0], count, rows_by_unit);
-    const int mask = (1 << t.digit_bits) - 1;
-    for (int p = 0; p < t.passes; ++p) {
-        const int shift = p * t.digit_bits;
+    const unsigned nj = (unsigned)njobs;
+    hipLaunchKernelGGL(schedule_clear_kernel, dim3(1), dim3(64), 0, s, kj, njobs);
+    hipLaunchKernelGGL(schedule_keys_kernel, dim3(max_units_blocks, nj), dim3(kSortBlock), 0, s, (int)m, (int)k, (int)nnz, rowptr,
+                       colind, kj);
+    const int mask = (1 << t[0].digit_bits) - 1;
+    for (int p = 0; p < t[0].passes; ++p) {
+        const int shift = p * t[0].digit_bits;
         const int in = p & 1, out = in ^ 1;
-        const bool last = p == t.passes - 1;
-        int* ids_out = last ? order : ids[out];
-        // the last pass delivers the first rows of the chunks, in schedule order, where the caller wants them
-        float* pad_out = (last && first_rows) ? reinterpret_cast<float*>(first_rows) : pad[out];
-        hipLaunchKernelGGL(radix_count_kernel, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys[in], n, shift, mask, hist, t.nblocks);
-        hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
-        hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(kSortBlock), 0, s, part, (int)t.parts);
-        hipLaunchKernelGGL(scan_apply_kernel, dim3((unsigned)t.parts), dim3(kSortBlock), 0, s, hist, t.hist_len, part);
-        hipLaunchKernelGGL(radix_scatter_kernel<false>, dim3(t.nblocks), dim3(kSortBlock), 0, s, keys[in], ids[in], pad[in], n,
-                           shift, mask, hist, t.nblocks, keys[out], ids_out, pad_out, (const int*)nullptr, 0);
+        const bool last = p == t[0].passes - 1;
+        SortJobs sj{};
+        for (int i = 0; i < njobs; ++i) {
+            char* ws = static_cast<char*>(jobs[i].workspace);
+            SortJob& S = sj.j[i];
+            S.keys_in = keys[i][in]; S.rows_in = ids[i][in]; S.vals_in = pad[i][in];
+            S.keys_out = keys[i][out];
+            S.rows_out = last ? jobs[i].order : ids[i][out];
+            // the last pass delivers the first rows of the chunks, in schedule order, where the caller wants them
+            S.vals_out = (last && jobs[i].first_rows) ? reinterpret_cast<float*>(jobs[i].first_rows) : pad[i][out];
+            S.hist = reinterpret_cast<int*>(ws + t[i].off_hist);
+            S.part = reinterpret_cast<int*>(ws + t[i].off_part);
+            S.hist_len = t[i].hist_len;
+            S.n = n[i]; S.nblocks = t[i].nblocks; S.parts = (int)t[i].parts;
+        }
+        hipLaunchKernelGGL(radix_count_jobs_kernel, dim3(max_nblocks, nj), dim3(kSortBlock), 0, s, sj, shift, mask);
+        hipLaunchKernelGGL(scan_reduce_jobs_kernel, dim3(max_parts, nj), dim3(kSortBlock), 0, s, sj);
+        hipLaunchKernelGGL(scan_top_jobs_kernel, dim3(nj), dim3(kSortBlock), 0, s, sj);
+        hipLaunchKernelGGL(scan_apply_jobs_kernel, dim3(max_parts, nj), dim3(kSortBlock), 0, s, sj);
+        hipLaunchKernelGGL(radix_scatter_jobs_kernel, dim3(max_nblocks, nj), dim3(kSortBlock), 0, s, sj, shift, mask);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "da_eb_schedule launch");
@@ -808,12 +843,12 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
     if (k > (1LL << 30)) { remember_nnz(rowptr, m, nnz); return DA_OK; }    // no schedule for such widths
     Plan pl;
     pl.rowptr = rowptr; pl.colind = colind; pl.m = m; pl.nnz = nnz;
-    size_t ints = 64, ws_bytes = 0;                        // the first 4 ints receive the segment sizes
+    size_t ints = 64, ws_bytes = 0, ws_off[4];             // the first 4 ints receive the segment sizes
     for (int i = 0; i < 4; ++i) {
         pl.units[i] = (int)((nnz + kPlanUnits[i] - 1) / kPlanUnits[i]);
         ints += 3 * (size_t)((pl.units[i] + 63) & ~63);     // the order and, twice, the first rows of the chunks
-        const size_t b = plan_transpose(2 * k, pl.units[i]).bytes;
-        ws_bytes = b > ws_bytes ? b : ws_bytes;
+        ws_off[i] = ws_bytes;                               // the four sorts run side by side, each in its own part
+        ws_bytes += align256(plan_transpose(2 * k, pl.units[i]).bytes);
     }
     pl.block = std::make_shared<DeviceBlock>();
     DeviceBlock ws;
@@ -821,19 +856,20 @@ int da_spmm_prepare(int64_t m, int64_t k, int64_t nnz, const int32_t* rowptr, co
     if (e != hipSuccess) return hip_fail(e, "hipMalloc");
     e = hipMalloc(&ws.p, ws_bytes);
     if (e != hipSuccess) return hip_fail(e, "hipMalloc");
-    int status = DA_OK;
     size_t off = 64;
     int* seg = static_cast<int*>(pl.block->p);
-    for (int i = 0; i < 4 && status == DA_OK; ++i) {
+    ScheduleJob jobs[4];
+    for (int i = 0; i < 4; ++i) {
         pl.order[i] = seg + off;
         off += (size_t)((pl.units[i] + 63) & ~63);
         pl.first_row[i] = seg + off;
         off += (size_t)((pl.units[i] + 63) & ~63);
         pl.row_by_chunk[i] = seg + off;
         off += (size_t)((pl.units[i] + 63) & ~63);
-        status = enqueue_schedule(m, k, nnz, rowptr, colind, kPlanUnits[i], pl.order[i], seg + i, pl.first_row[i],
-                                  pl.row_by_chunk[i], ws.p, ws_bytes, stream);
+        jobs[i] = ScheduleJob{kPlanUnits[i], pl.order[i], seg + i, pl.first_row[i], pl.row_by_chunk[i],
+                              static_cast<char*>(ws.p) + ws_off[i], ws_bytes - ws_off[i]};
     }
+    int status = enqueue_schedules(m, k, nnz, rowptr, colind, jobs, 4, stream);
     e = hipSuccess;
     if (status == DA_OK)
         e = hipMemcpyAsync(pl.first_units, seg, sizeof pl.first_units, hipMemcpyDeviceToHost, (hipStream_t)stream);

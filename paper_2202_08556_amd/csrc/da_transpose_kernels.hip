@@ -84,11 +84,11 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* sh, int* total) 
 // exclusive prefix sum of an int array, in place: reduce per chunk, scan the chunk sums in one
 // block, then scan every chunk with its base
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSortBlock) void scan_reduce_kernel(const int* __restrict__ data, long len,
-                                                                 int* __restrict__ part)
+__device__ __forceinline__ void scan_reduce_body(unsigned bx, const int* __restrict__ data, long len,
+                                                 int* __restrict__ part)
 {
     __shared__ int sh[kSortWaves];
-    const long base = (long)blockIdx.x * kScanChunk;
+    const long base = (long)bx * kScanChunk;
     int s = 0;
     for (int j = 0; j < kScanPerThread; ++j) {
         const long i = base + j * kSortBlock + threadIdx.x;
@@ -96,10 +96,16 @@ __global__ __launch_bounds__(kSortBlock) void scan_reduce_kernel(const int* __re
     }
     int total;
     block_exclusive_scan(s, sh, &total);
-    if (threadIdx.x == 0) part[blockIdx.x] = total;
+    if (threadIdx.x == 0) part[bx] = total;
 }
 
-__global__ __launch_bounds__(kSortBlock) void scan_top_kernel(int* __restrict__ part, int count)
+__global__ __launch_bounds__(kSortBlock) void scan_reduce_kernel(const int* __restrict__ data, long len,
+                                                                 int* __restrict__ part)
+{
+    scan_reduce_body(blockIdx.x, data, len, part);
+}
+
+__device__ __forceinline__ void scan_top_body(int* __restrict__ part, int count)
 {
     __shared__ int sh[kSortWaves];
     int carry = 0;
@@ -113,11 +119,16 @@ __global__ __launch_bounds__(kSortBlock) void scan_top_kernel(int* __restrict__ 
     }
 }
 
-__global__ __launch_bounds__(kSortBlock) void scan_apply_kernel(int* __restrict__ data, long len,
-                                                                const int* __restrict__ part)
+__global__ __launch_bounds__(kSortBlock) void scan_top_kernel(int* __restrict__ part, int count)
+{
+    scan_top_body(part, count);
+}
+
+__device__ __forceinline__ void scan_apply_body(unsigned bx, int* __restrict__ data, long len,
+                                                const int* __restrict__ part)
 {
     __shared__ int sh[kSortWaves];
-    const long first = (long)blockIdx.x * kScanChunk + (long)threadIdx.x * kScanPerThread;
+    const long first = (long)bx * kScanChunk + (long)threadIdx.x * kScanPerThread;
     int x[kScanPerThread];
     int s = 0;
 #pragma unroll
@@ -126,12 +137,18 @@ __global__ __launch_bounds__(kSortBlock) void scan_apply_kernel(int* __restrict_
         s += x[j];
     }
     int total;
-    int run = part[blockIdx.x] + block_exclusive_scan(s, sh, &total);
+    int run = part[bx] + block_exclusive_scan(s, sh, &total);
 #pragma unroll
     for (int j = 0; j < kScanPerThread; ++j) {
         if (first + j < len) data[first + j] = run;
         run += x[j];
     }
+}
+
+__global__ __launch_bounds__(kSortBlock) void scan_apply_kernel(int* __restrict__ data, long len,
+                                                                const int* __restrict__ part)
+{
+    scan_apply_body(blockIdx.x, data, len, part);
 }
 
 // Smallest r in [lo, hi] with rowptr[r+1] > e: the row that owns stored entry e, given that it
@@ -147,14 +164,14 @@ __device__ __forceinline__ int owner_row(const int* __restrict__ rowptr, int lo,
 // ------------------------------------------------------------------------------------------
 // one radix pass; digit = (key >> shift) & mask with mask < kBins
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSortBlock) void radix_count_kernel(const int* __restrict__ keys, int n, int shift, int mask,
-                                                                 int* __restrict__ hist, int nblocks)
+__device__ __forceinline__ void radix_count_body(unsigned bx, const int* __restrict__ keys, int n, int shift, int mask,
+                                                 int* __restrict__ hist, int nblocks)
 {
     __shared__ int cnt[kBins];
     cnt[threadIdx.x] = 0;
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long wbase = (long)blockIdx.x * kSortTile + (long)wave * kSortWaveRun;
+    const long wbase = (long)bx * kSortTile + (long)wave * kSortWaveRun;
     int key[kSortRounds];
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {               // all loads of the lane in flight together;
@@ -170,15 +187,21 @@ __global__ __launch_bounds__(kSortBlock) void radix_count_kernel(const int* __re
         __builtin_amdgcn_sched_barrier(0);                // keep the ballots of one round together
     }
     __syncthreads();
-    hist[(long)threadIdx.x * nblocks + blockIdx.x] = cnt[threadIdx.x];
+    hist[(long)threadIdx.x * nblocks + bx] = cnt[threadIdx.x];
+}
+
+__global__ __launch_bounds__(kSortBlock) void radix_count_kernel(const int* __restrict__ keys, int n, int shift, int mask,
+                                                                 int* __restrict__ hist, int nblocks)
+{
+    radix_count_body(blockIdx.x, keys, n, shift, mask, hist, nblocks);
 }
 
 // hist holds the exclusive prefix sums of the pass's histograms.  FIRST: the input is the matrix
 // itself (keys_in = colind, vals_in = vals) and the row number of an entry is derived from rowptr;
 // otherwise rows_in carries it.  The outputs of the last pass are the arrays of A^T.
 template <bool FIRST>
-__global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
-    const int* __restrict__ keys_in, const int* __restrict__ rows_in, const float* __restrict__ vals_in, int n,
+__device__ __forceinline__ void radix_scatter_body(
+    unsigned bx, const int* __restrict__ keys_in, const int* __restrict__ rows_in, const float* __restrict__ vals_in, int n,
     int shift, int mask, const int* __restrict__ hist, int nblocks,
     int* __restrict__ keys_out, int* __restrict__ rows_out, float* __restrict__ vals_out,
     const int* __restrict__ rowptr, int m)
@@ -192,7 +215,7 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int w = 0; w < kSortWaves; ++w) wcnt[w][threadIdx.x] = 0;
-    const long tbase = (long)blockIdx.x * kSortTile;
+    const long tbase = (long)bx * kSortTile;
     const long wbase = tbase + (long)wave * kSortWaveRun;
     const int tile_count = (int)min((long)kSortTile, (long)n - tbase);
     // the lane's 16 entries: every load is issued before the first one is used (indices clamped to
@@ -252,7 +275,7 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
         for (int w = 0; w < kSortWaves; ++w) { c[w] = wcnt[w][d]; total += c[w]; }
         int all;
         int slot = block_exclusive_scan(total, sh, &all);
-        gbase[d] = hist[(long)d * nblocks + blockIdx.x] - slot;
+        gbase[d] = hist[(long)d * nblocks + bx] - slot;
 #pragma unroll
         for (int w = 0; w < kSortWaves; ++w) { wcnt[w][d] = slot; slot += c[w]; }
     }
@@ -285,6 +308,17 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
     }
 }
 
+template <bool FIRST>
+__global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
+    const int* __restrict__ keys_in, const int* __restrict__ rows_in, const float* __restrict__ vals_in, int n,
+    int shift, int mask, const int* __restrict__ hist, int nblocks,
+    int* __restrict__ keys_out, int* __restrict__ rows_out, float* __restrict__ vals_out,
+    const int* __restrict__ rowptr, int m)
+{
+    radix_scatter_body<FIRST>(blockIdx.x, keys_in, rows_in, vals_in, n, shift, mask, hist, nblocks, keys_out, rows_out,
+                              vals_out, rowptr, m);
+}
+
 // Sort keys of the EB schedule for unit u (the stored entries [u*unit, (u+1)*unit)), in [0, 2k).
 // A unit inside one row covers a narrow column range and is keyed by the middle of that range,
 // k + (first + last column index)/2: these units are swept over B in column order.  A unit that
@@ -298,15 +332,66 @@ __global__ __launch_bounds__(kSortBlock) void radix_scatter_kernel(
 // ids = 0, 1, 2, ...; the value slot of the triples the radix passes move carries, as a bit pattern,
 // the row that owns the unit's first entry, so that the sort also delivers those rows in schedule order;
 // rows_by_unit (may be null) receives the same rows indexed by unit number.
-__global__ void schedule_clear_kernel(int* __restrict__ count) { *count = 0; }
+//
+// Several schedules (one per chunk size) are built side by side: every kernel of the pipeline takes
+// up to kMaxSortJobs jobs and blockIdx.y selects the job, so that the orders for all chunk sizes of
+// a matrix cost the launches of one.
+constexpr int kMaxSortJobs = 4;
+
+struct SortJob {                       // one radix pass of one job (pointers change from pass to pass)
+    const int* keys_in; const int* rows_in; const float* vals_in;
+    int* keys_out; int* rows_out; float* vals_out;
+    int* hist; int* part;
+    long hist_len;
+    int n, nblocks, parts;
+};
+struct SortJobs { SortJob j[kMaxSortJobs]; };
+
+struct KeyJob {                        // key generation of one schedule
+    int unit, nunits;
+    int* keys; int* ids; float* pad; int* count; int* rows_by_unit;
+};
+struct KeyJobs { KeyJob j[kMaxSortJobs]; };
+
+__global__ void schedule_clear_kernel(KeyJobs jobs, int njobs) {
+    if ((int)threadIdx.x < njobs) *jobs.j[threadIdx.x].count = 0;
+}
+
+__global__ __launch_bounds__(kSortBlock) void radix_count_jobs_kernel(SortJobs jobs, int shift, int mask) {
+    const SortJob J = jobs.j[blockIdx.y];
+    if ((int)blockIdx.x < J.nblocks) radix_count_body(blockIdx.x, J.keys_in, J.n, shift, mask, J.hist, J.nblocks);
+}
+__global__ __launch_bounds__(kSortBlock) void scan_reduce_jobs_kernel(SortJobs jobs) {
+    const SortJob J = jobs.j[blockIdx.y];
+    if ((int)blockIdx.x < J.parts) scan_reduce_body(blockIdx.x, J.hist, J.hist_len, J.part);
+}
+__global__ __launch_bounds__(kSortBlock) void scan_top_jobs_kernel(SortJobs jobs) {
+    const SortJob J = jobs.j[blockIdx.x];
+    scan_top_body(J.part, J.parts);
+}
+__global__ __launch_bounds__(kSortBlock) void scan_apply_jobs_kernel(SortJobs jobs) {
+    const SortJob J = jobs.j[blockIdx.y];
+    if ((int)blockIdx.x < J.parts) scan_apply_body(blockIdx.x, J.hist, J.hist_len, J.part);
+}
+__global__ __launch_bounds__(kSortBlock) void radix_scatter_jobs_kernel(SortJobs jobs, int shift, int mask) {
+    const SortJob J = jobs.j[blockIdx.y];
+    if ((int)blockIdx.x < J.nblocks)
+        radix_scatter_body<false>(blockIdx.x, J.keys_in, J.rows_in, J.vals_in, J.n, shift, mask, J.hist, J.nblocks, J.keys_out,
+                                  J.rows_out, J.vals_out, nullptr, 0);
+}
 
 __global__ __launch_bounds__(kSortBlock) void schedule_keys_kernel(int m, int k, int nnz, const int* __restrict__ rowptr,
-                                                                   const int* __restrict__ colind, int unit, int nunits,
-                                                                   int* __restrict__ keys, int* __restrict__ ids,
-                                                                   float* __restrict__ pad, int* __restrict__ count,
-                                                                   int* __restrict__ rows_by_unit)
+                                                                   const int* __restrict__ colind, KeyJobs jobs)
 {
+    const KeyJob J = jobs.j[blockIdx.y];
+    const int unit = J.unit, nunits = J.nunits;
+    int* __restrict__ keys = J.keys;
+    int* __restrict__ ids = J.ids;
+    float* __restrict__ pad = J.pad;
+    int* __restrict__ count = J.count;
+    int* __restrict__ rows_by_unit = J.rows_by_unit;
     const long u = (long)blockIdx.x * kSortBlock + threadIdx.x;
+    if ((long)blockIdx.x * kSortBlock >= nunits) return;          // whole block beyond this job's units
     bool several = false;
     if (u < nunits) {
         const long c0 = u * unit;
